@@ -1,0 +1,190 @@
+/* skippipe.h - C boundary of the MI355X library for path-routed LLaMa stage training.
+ *
+ * The method (SkipPipe, sections "System Setting", "Partial pipeline schedule" and
+ * "Guideline for Partial Pipelining Scheduler"): a model of L layers is cut into
+ * s equal stages of consecutive layers; every microbatch of an iteration carries
+ * a path, an ordered list of stage indices that opens with stage 0, and runs the
+ * forward pass through exactly those stages, in that order.  A stage that is not
+ * on the path is never applied, so the residual stream passes it unchanged.  The
+ * loss is taken after the last stage of the path, the backward pass walks the
+ * same stages in reverse, and the gradients of all microbatches are summed
+ * before any update.
+ *
+ * Conventions
+ *   - Every function returns 0 (SP_OK) or a negative sp_status; no exceptions and
+ *     no C++ types cross this boundary.  sp_strerror() names a code; after
+ *     SP_EHIP it also carries the HIP runtime's message.
+ *   - Pointers are DEVICE pointers unless the parameter is marked "host".
+ *   - All device work is enqueued on the HIP stream given to sp_create(); only
+ *     sp_run_paths() waits for it (to hand back the loss).
+ *   - The caller owns parameters, tokens, activation pools and gradients.  The
+ *     library owns only what sp_create() allocated and frees it in sp_destroy().
+ *   - Tensors are row-major, tokens-by-features.  A microbatch is seqs_per_mb
+ *     sequences of seq_len tokens: N_mb = seqs_per_mb * seq_len rows.
+ *   - dtype SP_F32: parameters and activations are float.  dtype SP_BF16:
+ *     parameters and activations are bfloat16 (the caller's rounding of its
+ *     float master copy); matrix products accumulate in float; norm statistics,
+ *     softmax, log-sum-exp and the loss are float.  Gradients of parameters are
+ *     float in both modes, in the parameter layout.
+ *
+ * Parameter layout (flat, element offsets from sp_param_layout):
+ *   [embed vocab x dim]                                      if has_embed
+ *   for each local stage, for each of its layers:
+ *     g1 (dim) | wqkv ((dim + 2*dkv) x dim) | wo (dim x dim) |
+ *     g2 (dim) | wgu (2*hidden x dim)       | wd (dim x hidden)
+ *   [gf (dim)] [whead vocab x dim]                           if has_head
+ *   Matrices are [out_features x in_features].  wqkv stacks query, key, value
+ *   rows; wgu stacks gate rows then up rows.  dkv = n_kv_heads * (dim / n_heads).
+ *   Query head a reads kv head a / (n_heads / n_kv_heads).  The rotary embedding
+ *   turns the pair (2i, 2i+1) of every query and key head at position p of its
+ *   sequence by p * rope_theta^(-2i/head_dim).
+ */
+#ifndef SKIPPIPE_H
+#define SKIPPIPE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum sp_status {
+  SP_OK = 0,
+  SP_EINVAL = -1, /* bad configuration, shape, index or null pointer */
+  SP_EPATH = -2,  /* a path violates the constraints in force */
+  SP_ENOMEM = -3, /* workspace exhausted or allocation failed */
+  SP_EHIP = -4,   /* a HIP runtime call failed */
+  SP_ESTATE = -5  /* call order: backward without the matching forward */
+} sp_status;
+
+enum { SP_F32 = 0, SP_BF16 = 1 };
+
+/* path_flags */
+enum {
+  SP_STRICT_CC = 0,      /* stage 0 first, increasing order with at most one exchange of two
+                            neighbouring entries whose stage indices differ by one */
+  SP_SWAP_ANY_GAP = 1,   /* the two exchanged neighbours may be any two stages */
+  SP_ALLOW_ANY_ORDER = 2 /* only: stage 0 first, no stage twice */
+};
+
+typedef struct sp_cfg {
+  int32_t dim, n_heads, n_kv_heads, hidden, vocab;
+  int32_t n_stages, layers_per_stage; /* equal stages of consecutive layers ("System Setting") */
+  int32_t seq_len, seqs_per_mb;
+  float rms_eps, rope_theta;
+  int32_t dtype;                                /* SP_F32 | SP_BF16 */
+  int32_t local_stage_begin, local_stage_count; /* stages whose weights this node holds */
+  int32_t has_embed, has_head;                  /* token embedding / final norm + output head + loss held here */
+  int32_t path_flags;
+} sp_cfg;
+
+typedef struct sp_tensor_desc {
+  char name[32];        /* "embed", "s<stage>.l<layer>.wqkv", "gf", "whead", ... */
+  int32_t stage, layer; /* -1 for tensors outside the stages */
+  int64_t offset;       /* in elements from the start of the flat buffer */
+  int64_t rows, cols;   /* vectors: rows = 1 */
+} sp_tensor_desc;
+
+typedef struct sp_ctx sp_ctx;
+
+/* ---- host-only helpers (no GPU needed) ---------------------------------------------------------- */
+
+/* Number of elements of the flat parameter (and gradient) buffer; negative sp_status on a bad cfg. */
+int64_t sp_param_count(const sp_cfg* cfg);
+
+/* Fills out[0..*n) with the tensors of the layout, in storage order.  cap = capacity of out (host);
+ * if cap is too small only *n is set and SP_EINVAL is returned. */
+int sp_param_layout(const sp_cfg* cfg, sp_tensor_desc* out, int cap, int* n);
+
+/* Device bytes sp_create(cfg, ., n_mb_max, n_visits_max, .) will allocate. */
+int64_t sp_workspace_bytes(const sp_cfg* cfg, int n_mb_max, int n_visits_max);
+
+/* Seeded paths honouring the convergence constraints CC1-CC3 of "Guideline for Partial
+ * Pipelining Scheduler" for a skip ratio k = skip_num / skip_den of the n_stages stages (stage 0
+ * counts in the denominator and is never skipped; section "Allocating Nodes to Stages", Eq. 1).
+ * Each path skips floor(s*k) or ceil(s*k) stages so that the total is round(n_mb*s*k); every stage
+ * i >= 1 is skipped by the same number of paths up to one.  allow_swap: a path may get one
+ * exchange of two neighbouring entries (strict form).  paths: host int32 [n_mb][n_stages], padded
+ * with -1; len: host int32 [n_mb].  Returns SP_EINVAL if k leaves no stage besides stage 0. */
+int sp_make_paths(int n_stages, int n_mb, int skip_num, int skip_den, int allow_swap, uint64_t seed,
+                  int32_t* paths, int32_t* len);
+
+/* Checks caller paths (host arrays as above) against cfg->path_flags: stage 0 first, no repeats,
+ * indices in range, order rule.  SP_EPATH names the first violation through sp_strerror. */
+int sp_check_paths(const sp_cfg* cfg, const int32_t* paths, const int32_t* len, int n_mb);
+
+/* Route plan: for every path position pos and stage st, the microbatches with paths[mb][pos]==st,
+ * restricted to local stages.  Groups are emitted by increasing pos, then stage; the forward pass
+ * runs them in this order, the backward pass in reverse.  group_pos/group_stage/group_begin: host
+ * int32 [cap_groups] (+1 for group_begin); group_mb: host int32 [n_mb*n_stages]. */
+int sp_route_plan(const sp_cfg* cfg, const int32_t* paths, const int32_t* len, int n_mb, int32_t* group_pos,
+                  int32_t* group_stage, int32_t* group_begin, int32_t* group_mb, int cap_groups, int* n_groups);
+
+const char* sp_strerror(int status);
+
+/* ---- device ------------------------------------------------------------------------------------ */
+
+/* Allocates the workspace on the current device: scratch for one group of up to n_mb_max
+ * microbatches, saved activations for up to n_visits_max (stage, microbatch) visits alive at once,
+ * and for a node holding embedding and head the two residual-stream pools sp_run_paths uses.
+ * hip_stream: a hipStream_t (0 = the null stream).  Nothing else is allocated later. */
+int sp_create(const sp_cfg* cfg, void* hip_stream, int n_mb_max, int n_visits_max, sp_ctx** out);
+int sp_destroy(sp_ctx* ctx);
+
+/* Forgets every saved forward (e.g. after an aborted iteration). */
+int sp_reset(sp_ctx* ctx);
+
+/* x[row, :] = embed[token[row], :] for n_mb microbatches (the front of stage 0).
+ * tokens: int32 [n_mb * N_mb]; act_pool: [n_mb][N_mb][dim] in cfg->dtype. */
+int sp_embed_fwd(sp_ctx* ctx, const void* params, const int32_t* tokens, int n_mb, void* act_pool);
+/* grads[embed][token[row], :] += dact[row, :]. */
+int sp_embed_bwd(sp_ctx* ctx, const int32_t* tokens, const void* dact_pool, int n_mb, float* grads);
+
+/* Forward of local stage `stage` (global index) for the group of microbatches mb_idx[0..n_group)
+ * (host int32, distinct slot numbers of act_pool), in place on their slots; every other slot is
+ * untouched (that is the skip).  The layers' intermediate results are kept inside ctx, keyed by
+ * (stage, group), until the matching sp_stage_bwd. */
+int sp_stage_fwd(sp_ctx* ctx, int stage, const void* params, void* act_pool, const int32_t* mb_idx, int n_group);
+
+/* Backward of the same group (same stage, same mb_idx in the same order; SP_ESTATE otherwise):
+ * dact_pool slots hold dL/d(output) on entry and dL/d(input) on return; parameter gradients are
+ * added into grads (float, parameter layout). */
+int sp_stage_bwd(sp_ctx* ctx, int stage, const void* params, void* dact_pool, const int32_t* mb_idx, int n_group,
+                 float* grads);
+
+/* Final norm, output head and next-token cross-entropy for all n_mb microbatches, forward and
+ * backward at once: loss_mb[mb] = mean over the targets >= 0 of microbatch mb; the iteration loss
+ * is their mean, so dact_pool receives d(mean)/d(act) = d(loss_mb)/d(act) / n_mb.  targets: int32
+ * [n_mb * N_mb], -1 = ignored.  loss_mb: device float [n_mb].  grads: += for gf and whead. */
+int sp_head_fwd_bwd(sp_ctx* ctx, const void* params, const void* act_pool, const int32_t* targets, int n_mb,
+                    float* loss_mb, void* dact_pool, float* grads);
+
+/* Whole model on this node (all stages local, embedding and head held): embeds, walks the route
+ * plan of the given paths (host arrays, checked against cfg->path_flags), takes the loss, walks
+ * the plan backwards, and returns the iteration loss.  grads is zeroed by the call.  loss_host:
+ * host float[1]; loss_mb_host: host float [n_mb] or NULL.  Waits for the stream. */
+int sp_run_paths(sp_ctx* ctx, const void* params, const int32_t* tokens, const int32_t* targets,
+                 const int32_t* paths, const int32_t* len, int n_mb, float* loss_host, float* loss_mb_host,
+                 float* grads);
+
+/* Matrix products used by the stages, exposed for unit tests and roofline measurement.
+ *   op 0: C[M,N]  = A[M,K] * B[N,K]^T  (+ R[M,N] if R != NULL)      C, R in cfg dtype
+ *   op 1: C[M,N]  = A[M,K] * B[K,N]                                  C in cfg dtype
+ *   op 2: C[M,N] += A[K,M]^T * B[K,N]                                C float
+ * A, B in dtype (SP_F32 / SP_BF16), row-major, dense leading dimensions. */
+int sp_gemm(void* hip_stream, int dtype, int op, int M, int N, int K, const void* A, const void* B, void* C,
+            const void* R);
+
+/* Causal attention used by the stages, exposed for unit tests and roofline measurement.
+ * qkv: [B*T][(H + 2*Hkv)*hd] rows of query|key|value; o: [B*T][H*hd]; lse: float [B][H][T].
+ * Backward: do_ like o; dqkv like qkv (overwritten). */
+int sp_attention_fwd(void* hip_stream, int dtype, int B, int T, int H, int Hkv, int hd, const void* qkv, void* o,
+                     float* lse);
+int sp_attention_bwd(void* hip_stream, int dtype, int B, int T, int H, int Hkv, int hd, const void* qkv,
+                     const void* o, const float* lse, const void* do_, void* dqkv, float* delta_scratch);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SKIPPIPE_H */

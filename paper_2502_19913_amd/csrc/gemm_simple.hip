@@ -1,0 +1,103 @@
+// Plain LDS-tiled matrix product with float accumulation for any shape, stride and element type.
+// It carries the float mode and every shape the MFMA kernels do not take; it is not the fast path.
+#include "devutil.h"
+#include "internal.h"
+
+namespace sp {
+
+namespace {
+
+constexpr int TM = 64, TN = 64, TK = 16;
+
+// C(m,n) = sum_k A(m,k) * B(k,n), A(m,k) = A[m*sam + k*sak], B(k,n) = B[k*sbk + n*sbn].
+// ACC: C is float and is added to.  Otherwise C is T and R (same shape, may be null) is added.
+template <class T, bool ACC>
+__global__ __launch_bounds__(256) void k_gemm_simple(const T* __restrict__ A, const T* __restrict__ B, void* Cv,
+                                                     const T* __restrict__ Rr, int64_t M, int64_t N, int64_t K,
+                                                     int64_t sam, int64_t sak, int64_t sbk, int64_t sbn) {
+  __shared__ float As[TK][TM + 1];
+  __shared__ float Bs[TK][TN + 1];
+  const int tid = threadIdx.x;
+  const int64_t m0 = (int64_t)blockIdx.y * TM, n0 = (int64_t)blockIdx.x * TN;
+  const int tx = tid % 16, ty = tid / 16;  // 4x4 outputs per thread: rows ty*4.., cols tx*4..
+  float acc[4][4] = {};
+  for (int64_t k0 = 0; k0 < K; k0 += TK) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      int e = tid + i * 256;
+      // fastest-varying index follows the contiguous dimension of each operand
+      int ka, ma, kb, nb;
+      if (sak == 1) { ka = e % TK; ma = e / TK; } else { ma = e % TM; ka = e / TM; }
+      if (sbk == 1) { kb = e % TK; nb = e / TK; } else { nb = e % TN; kb = e / TN; }
+      int64_t gm = m0 + ma, gk = k0 + ka;
+      As[ka][ma] = (gm < M && gk < K) ? to_float(A[gm * sam + gk * sak]) : 0.f;
+      int64_t gn = n0 + nb, gk2 = k0 + kb;
+      Bs[kb][nb] = (gn < N && gk2 < K) ? to_float(B[gk2 * sbk + gn * sbn]) : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < TK; ++k) {
+      float a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { a[i] = As[k][ty * 4 + i]; b[i] = Bs[k][tx * 4 + i]; }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] += a[i] * b[j];
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int64_t m = m0 + ty * 4 + i, n = n0 + tx * 4 + j;
+      if (m < M && n < N) {
+        if (ACC) {
+          float* C = (float*)Cv;
+          C[m * N + n] += acc[i][j];
+        } else {
+          T* C = (T*)Cv;
+          float v = acc[i][j];
+          if (Rr) v += to_float(Rr[m * N + n]);
+          C[m * N + n] = from_float<T>(v);
+        }
+      }
+    }
+}
+
+template <class T>
+void launch(hipStream_t s, int op, int64_t M, int64_t N, int64_t K, const void* A, const void* B, void* C,
+            const void* R) {
+  dim3 grid((unsigned)((N + TN - 1) / TN), (unsigned)((M + TM - 1) / TM));
+  if (op == 0)
+    hipLaunchKernelGGL((k_gemm_simple<T, false>), grid, dim3(256), 0, s, (const T*)A, (const T*)B, C, (const T*)R, M,
+                       N, K, K, (int64_t)1, (int64_t)1, K);
+  else if (op == 1)
+    hipLaunchKernelGGL((k_gemm_simple<T, false>), grid, dim3(256), 0, s, (const T*)A, (const T*)B, C, (const T*)nullptr,
+                       M, N, K, K, (int64_t)1, N, (int64_t)1);
+  else
+    hipLaunchKernelGGL((k_gemm_simple<T, true>), grid, dim3(256), 0, s, (const T*)A, (const T*)B, C, (const T*)nullptr,
+                       M, N, K, (int64_t)1, M, N, (int64_t)1);
+}
+
+}  // namespace
+
+void gemm_simple(hipStream_t s, int dtype, int op, int64_t M, int64_t N, int64_t K, const void* A, const void* B,
+                 void* C, const void* R) {
+  if (M <= 0 || N <= 0) return;
+  if (dtype == SP_BF16) launch<bf16>(s, op, M, N, K, A, B, C, R);
+  else launch<float>(s, op, M, N, K, A, B, C, R);
+}
+
+int gemm(hipStream_t s, int dtype, int op, int64_t M, int64_t N, int64_t K, const void* A, const void* B, void* C,
+         const void* R) {
+  if (op < 0 || op > 2 || M < 0 || N < 0 || K < 0) return fail(SP_EINVAL, "gemm: bad op or shape");
+  if ((M > 0 && N > 0) && (!C || (K > 0 && (!A || !B)))) return fail(SP_EINVAL, "gemm: null operand");
+  if (M == 0 || N == 0) return SP_OK;
+  if (dtype == SP_BF16 && gemm_mfma_supported(op, M, N, K, A, B, C, R)) gemm_mfma(s, op, M, N, K, A, B, C, R);
+  else gemm_simple(s, dtype, op, M, N, K, A, B, C, R);
+  return SP_OK;
+}
+
+}  // namespace sp

@@ -1,0 +1,85 @@
+// Declarations shared by the library's translation units (not part of the public boundary).
+#pragma once
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "../../include/skippipe.h"
+
+typedef struct ihipStream_t* hipStream_t;
+
+namespace sp {
+
+// ---- error plumbing
+int fail(int code, const std::string& msg);
+int check_cfg(const sp_cfg* c);
+int hip_fail(int hip_error, const char* what);  // records the HIP message, returns SP_EHIP
+
+// ---- flat parameter layout
+struct LayerOff { int64_t g1, wqkv, wo, g2, wgu, wd; };
+struct Layout {
+  int64_t embed = 0, gf = 0, whead = 0, total = 0;
+  std::vector<LayerOff> layers;  // local layers, stage-major
+  std::vector<sp_tensor_desc> tensors;
+};
+Layout make_layout(const sp_cfg& c);
+
+// ---- routing
+struct Group { int pos, stage; std::vector<int> mb; };
+int check_one_path(const sp_cfg& c, const int32_t* p, int len, int mb);
+int build_plan(const sp_cfg& c, const int32_t* paths, const int32_t* len, int n_mb, std::vector<Group>& out);
+
+inline int64_t elt_size(int dtype) { return dtype == SP_BF16 ? 2 : 4; }
+
+// Up to this many microbatches may share one group (slot numbers travel as a kernel argument).
+constexpr int kMaxGroup = 64;
+struct SlotList { int32_t n; int32_t slot[kMaxGroup]; };
+
+// ---- kernel launchers (all asynchronous on `s`; dtype is SP_F32 or SP_BF16)
+void embed_fwd(hipStream_t s, int dtype, const void* E, const int32_t* tok, int64_t rows, int d, void* x);
+void embed_bwd(hipStream_t s, int dtype, const void* dx, const int32_t* tok, int64_t rows, int d, float* dE);
+// dst[g*rows_per_slot + r, :] = pool[slot[g]*rows_per_slot + r, :]   (and the reverse)
+void gather_slots(hipStream_t s, int dtype, const void* pool, const SlotList& sl, int64_t rows_per_slot, int d, void* dst);
+void scatter_slots(hipStream_t s, int dtype, const void* src, const SlotList& sl, int64_t rows_per_slot, int d, void* pool);
+void fill_zero(hipStream_t s, void* p, int64_t bytes);
+
+void rmsnorm_fwd(hipStream_t s, int dtype, const void* x, const void* g, int64_t R, int d, float eps, void* y, float* rstd);
+// dx = (dres ? dres : 0) + rmsnorm'(dy) ; dg += sum_rows dy * x * rstd
+void rmsnorm_bwd(hipStream_t s, int dtype, const void* dy, const void* x, const void* g, const float* rstd,
+                 const void* dres, int64_t R, int d, void* dx, float* dg);
+// rotates the first nheads*hd columns of every row (row_stride elements apart); position = row % T
+void rope(hipStream_t s, int dtype, void* qk, int64_t R, int T, int nheads, int hd, int row_stride, float theta, int sign);
+void swiglu_fwd(hipStream_t s, int dtype, const void* gu, int64_t R, int h, void* a);
+void swiglu_bwd(hipStream_t s, int dtype, const void* da, const void* gu, int64_t R, int h, void* dgu);
+// counts[mb] = number of targets >= 0 among the rows of microbatch mb
+void count_targets(hipStream_t s, const int32_t* tgt, int n_mb, int64_t rows_per_mb, int32_t* counts);
+// rows [row0, row0+R) of the iteration: logits -> dlogits in place, loss_mb[mb] += rowloss / counts[mb]
+void cross_entropy(hipStream_t s, int dtype, void* logits, const int32_t* tgt, int64_t row0, int64_t R, int V,
+                   int64_t rows_per_mb, const int32_t* counts, float inv_n_mb, float* loss_mb);
+
+// C = A*B^T (+R) | C = A*B | C += A^T*B  (see sp_gemm); returns SP_EINVAL for bad arguments
+int gemm(hipStream_t s, int dtype, int op, int64_t M, int64_t N, int64_t K, const void* A, const void* B, void* C,
+         const void* R);
+
+int attention_fwd(hipStream_t s, int dtype, int B, int T, int H, int Hkv, int hd, const void* qkv, void* o, float* lse);
+int attention_bwd(hipStream_t s, int dtype, int B, int T, int H, int Hkv, int hd, const void* qkv, const void* o,
+                  const float* lse, const void* do_, void* dqkv, float* delta);
+
+// building blocks the dispatchers choose between
+void gemm_simple(hipStream_t s, int dtype, int op, int64_t M, int64_t N, int64_t K, const void* A, const void* B,
+                 void* C, const void* R);
+bool gemm_mfma_supported(int op, int64_t M, int64_t N, int64_t K, const void* A, const void* B, const void* C,
+                         const void* R);
+void gemm_mfma(hipStream_t s, int op, int64_t M, int64_t N, int64_t K, const void* A, const void* B, void* C,
+               const void* R);
+void attention_simple_fwd(hipStream_t s, int dtype, int B, int T, int H, int Hkv, int hd, const void* qkv, void* o,
+                          float* lse);
+void attention_simple_bwd(hipStream_t s, int dtype, int B, int T, int H, int Hkv, int hd, const void* qkv,
+                          const void* o, const float* lse, const void* do_, void* dqkv, float* delta);
+bool attention_flash_supported(int B, int T, int H, int Hkv, int hd);
+void attention_flash_fwd(hipStream_t s, int B, int T, int H, int Hkv, int hd, const void* qkv, void* o, float* lse);
+void attention_flash_bwd(hipStream_t s, int B, int T, int H, int Hkv, int hd, const void* qkv, const void* o,
+                         const float* lse, const void* do_, void* dqkv, float* delta);
+
+}  // namespace sp
