@@ -1,0 +1,126 @@
+"""Single GPU kernels against the CPU checker's ops: matrix products in the three layouts and causal
+attention forward/backward, at sizes that span several tiles with ragged edges."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import skippipe_oracle as orc
+from paper_2502_19913_amd import binding as sp
+from paper_2502_19913_amd import synth
+from tests.gpuharness import cosine, relerr, round_bf16
+
+pytestmark = pytest.mark.gpu
+
+
+def dev(a, dt):
+    return torch.from_numpy(np.ascontiguousarray(a, np.float32)).cuda().to(dt)
+
+
+GEMM_SHAPES = [
+    (256, 256, 64), (512, 768, 256), (300, 520, 136), (64, 288, 288), (1, 8, 8), (257, 264, 72),
+    (1000, 40, 1024), (128, 864, 288), (2048, 2048, 512), (72, 1032, 2056),
+]
+
+
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_gemm_three_layouts(M, N, K, dtype):
+    dt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    rnd = round_bf16 if dtype == "bf16" else (lambda a: a)
+    tol = 4e-3 if dtype == "bf16" else 2e-5
+    a = rnd(synth.normal(1, f"a{M}{N}{K}", (M, K)))
+    b = rnd(synth.normal(2, f"b{M}{N}{K}", (N, K)))
+    r = rnd(synth.normal(3, f"r{M}{N}{K}", (M, N)))
+    a64, b64, r64 = a.astype(np.float64), b.astype(np.float64), r.astype(np.float64)
+    # op 0 with and without the added matrix; reference is the checker's linear (x W^T)
+    ref0 = orc.linear_fwd(a64, b64)
+    c = torch.full((M, N), 7.0, dtype=dt, device="cuda")
+    sp.gemm(0, dev(a, dt), dev(b, dt), c)
+    assert relerr(c.float().cpu().numpy(), ref0) < tol
+    sp.gemm(0, dev(a, dt), dev(b, dt), c, dev(r, dt))
+    assert relerr(c.float().cpu().numpy(), ref0 + r64) < tol
+    # op 1: C = A B with B [K, N]; reference dx = dy W of the checker (dy = a, W = b^T stored [K, N])
+    bt = np.ascontiguousarray(b.T)                                   # [K, N]
+    ref1 = a64 @ bt.astype(np.float64)
+    c1 = torch.full((M, N), -3.0, dtype=dt, device="cuda")
+    sp.gemm(1, dev(a, dt), dev(bt, dt), c1)
+    assert relerr(c1.float().cpu().numpy(), ref1) < tol
+    # op 2: C += A^T B with A [K, M], B [K, N]; the checker's dW = dy^T x
+    at = np.ascontiguousarray(a.T)                                   # [K, M]
+    init = synth.normal(4, f"i{M}{N}{K}", (M, N))
+    _, ref2 = orc.linear_bwd(at.astype(np.float64), bt.astype(np.float64), np.zeros((M, N)))
+    c2 = dev(init, torch.float32)
+    sp.gemm(2, dev(at, dt), dev(bt, dt), c2)
+    got2 = c2.cpu().numpy().astype(np.float64) - init
+    assert relerr(got2, ref2) < (2e-5 if dtype == "f32" else 2e-5), (relerr(got2, ref2))
+
+
+def test_gemm_long_reduction_split():
+    # the weight-gradient shape: reduction over tokens, few output tiles
+    K, M, N = 8192, 512, 264
+    a = round_bf16(synth.normal(5, "la", (K, M))); b = round_bf16(synth.normal(6, "lb", (K, N)))
+    c = torch.zeros((M, N), dtype=torch.float32, device="cuda")
+    sp.gemm(2, dev(a, torch.bfloat16), dev(b, torch.bfloat16), c)
+    ref = a.astype(np.float64).T @ b.astype(np.float64)
+    assert relerr(c.cpu().numpy(), ref) < 1e-5
+    sp.gemm(2, dev(a, torch.bfloat16), dev(b, torch.bfloat16), c)       # accumulates
+    assert relerr(c.cpu().numpy(), 2 * ref) < 1e-5
+
+
+def test_gemm_rejects_bad_arguments():
+    a = torch.zeros((8, 8), device="cuda")
+    with pytest.raises(sp.SpError):
+        sp._check(sp.lib().sp_gemm(None, 0, 5, 8, 8, 8, sp._dptr(a), sp._dptr(a), sp._dptr(a), None))
+    with pytest.raises(sp.SpError):
+        sp._check(sp.lib().sp_gemm(None, 0, 0, 8, 8, 8, None, sp._dptr(a), sp._dptr(a), None))
+
+
+ATTN_CASES = [  # B, T, H, Hkv, hd
+    (2, 64, 6, 6, 48), (1, 200, 4, 2, 64), (2, 333, 4, 1, 128), (1, 1, 2, 2, 64), (3, 17, 2, 1, 10),
+    (1, 512, 2, 2, 128), (1, 640, 4, 4, 64),
+]
+
+
+@pytest.mark.parametrize("B,T,H,Hkv,hd", ATTN_CASES)
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_attention_forward_backward(B, T, H, Hkv, hd, dtype):
+    dt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    rnd = round_bf16 if dtype == "bf16" else (lambda a: a)
+    nq = (H + 2 * Hkv) * hd
+    qkv = rnd(synth.normal(7, f"qkv{B}{T}{H}{hd}", (B * T, nq)))
+    do = rnd(synth.normal(8, f"do{B}{T}{H}{hd}", (B * T, H * hd)))
+    q = np.ascontiguousarray(qkv[:, :H * hd]).reshape(B * T, H, hd).astype(np.float64)
+    k = np.ascontiguousarray(qkv[:, H * hd:(H + Hkv) * hd]).reshape(B * T, Hkv, hd).astype(np.float64)
+    v = np.ascontiguousarray(qkv[:, (H + Hkv) * hd:]).reshape(B * T, Hkv, hd).astype(np.float64)
+    o_ref = orc.attention_fwd(q, k, v, B, T)
+    dq, dk, dv = orc.attention_bwd(do.reshape(B * T, H, hd).astype(np.float64), q, k, v, B, T)
+    dqkv_ref = np.concatenate([dq.reshape(B * T, -1), dk.reshape(B * T, -1), dv.reshape(B * T, -1)], axis=1)
+
+    d_qkv = dev(qkv, dt)
+    o = torch.empty((B * T, H * hd), dtype=dt, device="cuda")
+    lse = torch.empty((B, H, T), dtype=torch.float32, device="cuda")
+    sp.attention_fwd(d_qkv, o, lse, B, T, H, Hkv, hd)
+    o_got = o.float().cpu().numpy().reshape(B * T, H, hd)
+    # log-sum-exp against its definition on a few rows
+    sc = np.einsum("thd,shd->hts", q[:T], np.repeat(k[:T], H // Hkv, axis=1)) / np.sqrt(hd)
+    for i in (0, T // 2, T - 1):
+        want = np.log(np.exp(sc[:, i, :i + 1] - sc[:, i, :i + 1].max(-1, keepdims=True)).sum(-1)) + sc[:, i, :i + 1].max(-1)
+        assert np.allclose(lse[0, :, i].cpu().numpy(), want, rtol=2e-2 if dtype == "bf16" else 1e-4, atol=2e-2 if dtype == "bf16" else 1e-5)
+    if dtype == "f32":
+        assert relerr(o_got, o_ref) < 1e-5
+    else:
+        assert relerr(o_got, o_ref) < 1e-2 and cosine(o_got, o_ref) > 0.9999
+    # backward uses the forward's own o (as the stage does)
+    dqkv = torch.empty((B * T, nq), dtype=dt, device="cuda")
+    delta = torch.empty((B * H * T,), dtype=torch.float32, device="cuda")
+    sp.attention_bwd(d_qkv, o, lse, dev(do, dt), dqkv, delta, B, T, H, Hkv, hd)
+    got = dqkv.float().cpu().numpy()
+    if dtype == "f32":
+        assert relerr(got, dqkv_ref) < 2e-5
+    else:
+        for lo, hi, nm in [(0, H * hd, "dq"), (H * hd, (H + Hkv) * hd, "dk"), ((H + Hkv) * hd, nq, "dv")]:
+            if not np.any(dqkv_ref[:, lo:hi]):     # T = 1: dq and dk vanish; only rounding noise may remain
+                assert np.abs(got[:, lo:hi]).max() <= 1e-2 * np.abs(dqkv_ref).max(), nm
+                continue
+            assert cosine(got[:, lo:hi], dqkv_ref[:, lo:hi]) > 0.9995, nm
+            assert relerr(got[:, lo:hi], dqkv_ref[:, lo:hi]) < 2e-2, nm
