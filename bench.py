@@ -1,0 +1,238 @@
+#!/usr/bin/env python3
+"""Throughput of the path-routed stage forward+backward on one MI355X.
+
+One step = one pass of the whole hot path over one batch of seeded synthetic input that is already
+resident in HBM: every group of the route plan through the stage forward, (for the head-holding
+workload) final norm + output head + loss, then every group through the stage backward, with the
+gradient buffer cleared at the start of the step.  Prints one JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c3|c2|c4|c5|c1]
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
+
+
+def flops_per_token_layer(cfg):
+    """Algorithmic forward flops of one decoder layer per token (causal attention counted on (T+1)/2 keys)."""
+    d, h, T = cfg["dim"], cfg["hidden"], cfg["seq_len"]
+    hd = d // cfg["n_heads"]
+    nq = d + 2 * cfg["n_kv_heads"] * hd
+    return 2 * d * nq + 2 * d * d + 6 * d * h + 2 * d * (T + 1)
+
+
+def build_workload(key, torch, sp, synth):
+    cfg = dict(synth.CONFIGS[key])
+    dev = "cuda"
+    dt = sp.torch_dtype(cfg)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(synth.BASE_SEED)
+    n_mb, Nmb, d = cfg["n_mb"], cfg["seqs_per_mb"] * cfg["seq_len"], cfg["dim"]
+    whole = bool(cfg["has_embed"] and cfg["has_head"])
+    if whole:
+        paths, lens = synth.make_paths(cfg["n_stages"], n_mb, *cfg["skip"], bool(cfg["swap"]), synth.BASE_SEED)
+        stage = None
+    else:
+        paths, lens, stage = synth.stage_share_paths(key)
+        cfg["local_stage_begin"], cfg["local_stage_count"] = stage, 1
+    plan = sp.route_plan(cfg, paths, lens)
+    visits = sum(len(m) for _, _, m in plan)
+    # parameters: N(0, 0.02) matrices, unit gains, generated on the device in the layout's order
+    params = torch.empty(sp.param_count(cfg), dtype=dt, device=dev)
+    for name, _, _, off, rows, cols in sp.param_layout(cfg):
+        v = params[off:off + rows * cols]
+        if rows == 1:
+            v.fill_(1.0)
+        else:
+            step = 1 << 26
+            for lo in range(0, rows * cols, step):
+                hi = min(rows * cols, lo + step)
+                v[lo:hi] = (torch.randn(hi - lo, generator=gen, device=dev, dtype=torch.float32) * 0.02).to(dt)
+    grads = torch.zeros(params.numel(), dtype=torch.float32, device=dev)
+    w = dict(cfg=cfg, key=key, paths=paths, lens=lens, plan=plan, visits=visits, params=params, grads=grads,
+             whole=whole, stage=stage)
+    if whole:
+        tok, tgt = synth.make_tokens(cfg, synth.BASE_SEED)
+        w["tok"] = torch.from_numpy(tok.reshape(-1)).to(dev)
+        w["tgt"] = torch.from_numpy(tgt.reshape(-1)).to(dev)
+    else:
+        w["act0"] = torch.randn(n_mb * Nmb * d, generator=gen, device=dev, dtype=torch.float32).to(dt)
+        w["act"] = torch.empty_like(w["act0"])
+        w["dact"] = torch.empty_like(w["act0"])
+        if cfg["has_head"]:
+            tok, tgt = synth.make_tokens(cfg, synth.BASE_SEED)
+            w["tgt"] = torch.from_numpy(tgt.reshape(-1)).to(dev)
+            w["loss_mb"] = torch.empty(n_mb, dtype=torch.float32, device=dev)
+        else:
+            w["dact0"] = (torch.randn(n_mb * Nmb * d, generator=gen, device=dev, dtype=torch.float32)
+                          / float(Nmb * n_mb)).to(dt)
+    w["ctx"] = sp.Context(cfg, n_mb, max(1, visits))
+    # algorithmic work of one step
+    per_tl = flops_per_token_layer(cfg)
+    fl = 3.0 * per_tl * cfg["layers_per_stage"] * visits * Nmb
+    if cfg["has_head"]:
+        fl += 3.0 * 2 * d * cfg["vocab"] * n_mb * Nmb
+    w["flops"] = fl
+    w["tokens_presented"] = n_mb * Nmb
+    w["stage_tokens"] = visits * Nmb
+    return w
+
+
+def step(w):
+    ctx, cfg = w["ctx"], w["cfg"]
+    if w["whole"]:
+        loss, _ = ctx.run_paths(w["params"], w["tok"], w["tgt"], w["paths"], w["lens"], w["grads"])
+        return loss
+    w["grads"].zero_()
+    w["act"].copy_(w["act0"])
+    for _, st, mbs in w["plan"]:
+        ctx.stage_fwd(st, w["params"], w["act"], mbs)
+    if cfg["has_head"]:
+        ctx.head_fwd_bwd(w["params"], w["act"], w["tgt"], cfg["n_mb"], w["loss_mb"], w["dact"], w["grads"])
+    else:
+        w["dact"].copy_(w["dact0"])
+    for _, st, mbs in reversed(w["plan"]):
+        ctx.stage_bwd(st, w["params"], w["dact"], mbs, w["grads"])
+    return None
+
+
+def cpu_baseline(key, synth):
+    """The CPU checker timed on a bounded sample of the same workload (float32 instantiation)."""
+    import numpy as np
+    from oracle import skippipe_oracle as orc
+    full = synth.CONFIGS[key]
+    lib = orc.lib()
+    try:
+        cores = int(ctypes.CDLL("libgomp.so.1").omp_get_max_threads())
+    except Exception:
+        cores = os.cpu_count() or 1
+    if full["has_embed"] and full["has_head"]:
+        # whole small model: keep widths and depth, cut tokens
+        T = min(full["seq_len"], 128 if full["dim"] > 512 else full["seq_len"])
+        cfg = synth.shrink(full, seq_len=T, seqs_per_mb=1, n_mb=min(2, full["n_mb"]),
+                           vocab=min(full["vocab"], 4096))
+        paths, lens = synth.make_paths(cfg["n_stages"], cfg["n_mb"], *cfg["skip"], bool(cfg["swap"]), synth.BASE_SEED)
+        named = synth.make_params(cfg, synth.BASE_SEED)
+        tok, tgt = synth.make_tokens(cfg, synth.BASE_SEED)
+        t0 = time.perf_counter()
+        orc.run_paths(cfg, named, paths, lens, tokens=tok, targets=tgt, dtype=np.float32)
+        dt = time.perf_counter() - t0
+        toks = cfg["n_mb"] * T
+        sample = (f"{cfg['n_mb']} microbatches x {T} tokens through the whole {full['n_stages']}-stage model "
+                  f"(full widths, vocab {cfg['vocab']}), fwd+bwd+loss")
+    else:
+        T = 2048 if full["dim"] <= 2048 else 512
+        cfg = synth.shrink(full, seq_len=T, seqs_per_mb=1, n_mb=1, has_head=0, vocab=1024)
+        _, _, stage = synth.stage_share_paths(key)
+        cfg["local_stage_begin"], cfg["local_stage_count"] = stage, 1
+        paths = np.full((1, cfg["n_stages"]), -1, np.int32)
+        paths[0, :2] = (0, stage)
+        lens = np.array([2], np.int32)
+        named = synth.make_params(cfg, synth.BASE_SEED)
+        x = synth.make_activations(cfg, synth.BASE_SEED)
+        dy = synth.make_upstream_grad(cfg, synth.BASE_SEED)
+        t0 = time.perf_counter()
+        orc.run_paths(cfg, named, paths, lens, x_in=x, dy_in=dy, dtype=np.float32)
+        dt = time.perf_counter() - t0
+        toks = T
+        sample = (f"1 microbatch x {T} tokens through the {cfg['layers_per_stage']}-layer stage (full widths), "
+                  f"fwd+bwd, no head")
+    return dict(value=toks / dt, unit="tokens/s", cores=cores, kind="oracle", sample=sample, seconds=round(dt, 2))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2502_19913_amd import binding as sp
+    from paper_2502_19913_amd import synth
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    w = build_workload(args.config, torch, sp, synth)
+    for _ in range(args.warmup):
+        step(w)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(w)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    sec = (t1 - t0) / args.steps
+
+    # second pass of the same steps with HIP events around every matrix-product and attention launch
+    sp.prof_begin()
+    for _ in range(args.steps):
+        step(w)
+    torch.cuda.synchronize()
+    prof = sp.prof_end()
+    gemm_cls = [k for k in ("gemm_nt", "gemm_nn", "gemm_tn") if prof[k]["launches"]]
+    roof = None
+    if gemm_cls:
+        dom = max(gemm_cls, key=lambda k: prof[k]["ms"])
+        p = prof[dom]
+        achieved = p["flops"] / (p["ms"] * 1e-3) / 1e12
+        roof = dict(bound="mfma", kernel={"gemm_nt": "k_gemm_mfma<0>", "gemm_nn": "k_gemm_mfma<1>",
+                                          "gemm_tn": "k_gemm_mfma<2>"}[dom],
+                    achieved=round(achieved, 1), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                    frac=round(achieved / PEAK_BF16_TFLOPS, 4), traffic=None,
+                    avg_launch_ms=round(p["ms"] / p["launches"], 4), launches_per_step=p["launches"] // args.steps,
+                    share_of_step=round(p["ms"] / args.steps / (sec * 1e3), 3))
+    kernels = {k: dict(ms_per_step=round(v["ms"] / args.steps, 3),
+                       tflops=round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 1) if v["ms"] > 0 else None,
+                       launches_per_step=v["launches"] // args.steps)
+               for k, v in prof.items() if v["launches"]}
+
+    cfg = w["cfg"]
+    tflops = w["flops"] / sec / 1e12
+    out = {
+        "metric": "path-routed stage fwd+bwd tokens/sec on 1 MI355X; % bf16 MFMA peak",
+        "value": round(w["tokens_presented"] / sec, 1),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(sec * 1e3, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg["dtype"] == "bf16" else "f32",
+        "data": "synthetic (seeded): N(0,0.02) weights, N(0,1) activations or uniform tokens, seeded paths",
+        "config": {"workload": {
+            "c1": "50M-shape whole model, 4 stages x 3 layers, 2 microbatches x 64 tokens, keep 3 of 4 stages",
+            "c2": "500M-shape whole model, 6 stages x 4 layers, 8 microbatches x 4 x 1024 tokens, 1/3 skip with swaps",
+            "c3": "1.5B-shape single stage of 4 layers (dim 2048, 16 heads, hidden 5632), 8 microbatches x 4096 tokens "
+                  "arriving at path positions 1/2/3 in groups of 3/3/2, stage fwd+bwd only",
+            "c4": "LLaMa-2-7B-shape single stage of 4 layers, 16 microbatches x 4096 tokens under 25% skip",
+            "c5": "LLaMa-3-8B-shape single stage of 4 layers (GQA) + final norm + LM head + CE, 16 microbatches x 4096 "
+                  "tokens under 1/3 skip with swaps",
+        }[args.config], "id": args.config, "n_mb": cfg["n_mb"], "tokens_per_mb": cfg["seqs_per_mb"] * cfg["seq_len"],
+            "stage_visits": w["visits"], "groups": [len(m) for _, _, m in w["plan"]]},
+        "stage_tokens_per_s": round(w["stage_tokens"] / sec, 1),
+        "tflops": round(tflops, 1),
+        "frac_bf16_mfma_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
+        "roofline": roof,
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.config, synth)
+    w["ctx"].close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -184,6 +184,15 @@ int sp_attention_fwd(void* hip_stream, int dtype, int B, int T, int H, int Hkv, 
 int sp_attention_bwd(void* hip_stream, int dtype, int B, int T, int H, int Hkv, int hd, const void* qkv,
                      const void* o, const float* lse, const void* do_, void* dqkv, float* delta_scratch);
 
+/* Measurement aid: between sp_prof_begin() and sp_prof_end() every matrix-product and attention
+ * launch of this process is bracketed by HIP events on its stream.  sp_prof_end waits for them and
+ * fills, per kernel class c < n_classes, the summed duration (ms), the summed algorithmic flops
+ * and the launch count (host arrays).  Classes: 0 C=A B^T, 1 C=A B, 2 C+=A^T B (MFMA kernels),
+ * 3 attention forward, 4 attention delta, 5 attention dQ, 6 attention dK/dV, 7 plain matrix
+ * product, 8 plain attention. */
+int sp_prof_begin(void);
+int sp_prof_end(int n_classes, double* ms, double* flops, int64_t* launches);
+
 #ifdef __cplusplus
 }
 #endif

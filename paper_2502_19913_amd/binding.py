@@ -22,7 +22,7 @@ SP_STRICT_CC, SP_SWAP_ANY_GAP, SP_ALLOW_ANY_ORDER = 0, 1, 2
 EXPORTS = ["sp_param_count", "sp_param_layout", "sp_workspace_bytes", "sp_make_paths", "sp_check_paths",
            "sp_route_plan", "sp_strerror", "sp_create", "sp_destroy", "sp_reset", "sp_embed_fwd", "sp_embed_bwd",
            "sp_stage_fwd", "sp_stage_bwd", "sp_head_fwd_bwd", "sp_run_paths", "sp_gemm", "sp_attention_fwd",
-           "sp_attention_bwd"]
+           "sp_attention_bwd", "sp_prof_begin", "sp_prof_end"]
 
 
 class SpCfg(C.Structure):
@@ -247,3 +247,18 @@ def attention_fwd(qkv, o, lse, B, T, H, Hkv, hd, stream=None):
 def attention_bwd(qkv, o, lse, do, dqkv, delta, B, T, H, Hkv, hd, stream=None):
     _check(lib().sp_attention_bwd(_stream_ptr(stream), C.c_int(_dt(qkv)), B, T, H, Hkv, hd, _dptr(qkv), _dptr(o),
                                   _dptr(lse), _dptr(do), _dptr(dqkv), _dptr(delta)))
+
+
+PROF_CLASSES = ["gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd", "attn_delta", "attn_dq", "attn_dkv", "gemm_plain",
+                "attn_plain"]
+
+
+def prof_begin():
+    _check(lib().sp_prof_begin())
+
+
+def prof_end() -> Dict[str, dict]:
+    n = len(PROF_CLASSES)
+    ms = np.zeros(n, np.float64); fl = np.zeros(n, np.float64); cnt = np.zeros(n, np.int64)
+    _check(lib().sp_prof_end(C.c_int(n), _iptr(ms), _iptr(fl), _iptr(cnt)))
+    return {PROF_CLASSES[i]: dict(ms=float(ms[i]), flops=float(fl[i]), launches=int(cnt[i])) for i in range(n)}

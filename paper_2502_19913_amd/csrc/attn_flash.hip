@@ -539,21 +539,33 @@ void attention_flash_bwd(hipStream_t s, int B, int T, int H, int Hkv, int hd, co
   const float scale = 1.0f / sqrtf((float)hd);
   const int64_t items = (int64_t)B * T * H;
   dim3 gq((T + 127) / 128, H, B), gk((T + 127) / 128, Hkv, B);
-  if (hd == 128) {
+  // algorithmic flops of the backward pass: four products (dV, dP, dQ, dK) over the causal half;
+  // dQ is credited to its kernel, the other three to the dK/dV kernel (the recomputed scores are not counted)
+  const double unit = (double)B * H * (double)T * (T + 1) * hd;
+  int pi = prof_start(PROF_ATTN_DELTA, s);
+  if (hd == 128)
     hipLaunchKernelGGL(k_flash_delta<128>, dim3((unsigned)((items * 16 + 255) / 256)), dim3(256), 0, s, (const bf16*)o,
                        (const bf16*)do_, B, T, H, delta);
-    hipLaunchKernelGGL(k_flash_bwd_dq<128>, gq, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)do_, lse, delta,
-                       (bf16*)dqkv, T, H, Hkv, scale);
-    hipLaunchKernelGGL(k_flash_bwd_dkv<128>, gk, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)do_, lse, delta,
-                       (bf16*)dqkv, T, H, Hkv, scale);
-  } else {
+  else
     hipLaunchKernelGGL(k_flash_delta<64>, dim3((unsigned)((items * 8 + 255) / 256)), dim3(256), 0, s, (const bf16*)o,
                        (const bf16*)do_, B, T, H, delta);
+  prof_stop(pi, s, 0.0);
+  pi = prof_start(PROF_ATTN_DQ, s);
+  if (hd == 128)
+    hipLaunchKernelGGL(k_flash_bwd_dq<128>, gq, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)do_, lse, delta,
+                       (bf16*)dqkv, T, H, Hkv, scale);
+  else
     hipLaunchKernelGGL(k_flash_bwd_dq<64>, gq, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)do_, lse, delta,
                        (bf16*)dqkv, T, H, Hkv, scale);
+  prof_stop(pi, s, unit);
+  pi = prof_start(PROF_ATTN_DKV, s);
+  if (hd == 128)
+    hipLaunchKernelGGL(k_flash_bwd_dkv<128>, gk, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)do_, lse, delta,
+                       (bf16*)dqkv, T, H, Hkv, scale);
+  else
     hipLaunchKernelGGL(k_flash_bwd_dkv<64>, gk, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)do_, lse, delta,
                        (bf16*)dqkv, T, H, Hkv, scale);
-  }
+  prof_stop(pi, s, 3.0 * unit);
 }
 
 }  // namespace sp

@@ -230,8 +230,11 @@ int attention_fwd(hipStream_t s, int dtype, int B, int T, int H, int Hkv, int hd
   int rc = check_attn(B, T, H, Hkv, hd);
   if (rc) return rc;
   if (!qkv || !o || !lse) return fail(SP_EINVAL, "attention: null operand");
-  if (dtype == SP_BF16 && attention_flash_supported(B, T, H, Hkv, hd)) attention_flash_fwd(s, B, T, H, Hkv, hd, qkv, o, lse);
+  const bool fast = dtype == SP_BF16 && attention_flash_supported(B, T, H, Hkv, hd);
+  const int pi = prof_start(fast ? PROF_ATTN_FWD : PROF_ATTN_PLAIN, s);
+  if (fast) attention_flash_fwd(s, B, T, H, Hkv, hd, qkv, o, lse);
   else attention_simple_fwd(s, dtype, B, T, H, Hkv, hd, qkv, o, lse);
+  prof_stop(pi, s, 2.0 * (double)B * H * (double)T * (T + 1) * hd);   // QK^T and PV over the causal half
   return SP_OK;
 }
 
@@ -240,10 +243,13 @@ int attention_bwd(hipStream_t s, int dtype, int B, int T, int H, int Hkv, int hd
   int rc = check_attn(B, T, H, Hkv, hd);
   if (rc) return rc;
   if (!qkv || !o || !lse || !do_ || !dqkv || !delta) return fail(SP_EINVAL, "attention: null operand");
-  if (dtype == SP_BF16 && attention_flash_supported(B, T, H, Hkv, hd))
+  if (dtype == SP_BF16 && attention_flash_supported(B, T, H, Hkv, hd)) {
     attention_flash_bwd(s, B, T, H, Hkv, hd, qkv, o, lse, do_, dqkv, delta);
-  else
+  } else {
+    const int pi = prof_start(PROF_ATTN_PLAIN, s);
     attention_simple_bwd(s, dtype, B, T, H, Hkv, hd, qkv, o, lse, do_, dqkv, delta);
+    prof_stop(pi, s, 4.0 * (double)B * H * (double)T * (T + 1) * hd);
+  }
   return SP_OK;
 }
 

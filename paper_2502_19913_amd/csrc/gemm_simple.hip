@@ -95,8 +95,11 @@ int gemm(hipStream_t s, int dtype, int op, int64_t M, int64_t N, int64_t K, cons
   if (op < 0 || op > 2 || M < 0 || N < 0 || K < 0) return fail(SP_EINVAL, "gemm: bad op or shape");
   if ((M > 0 && N > 0) && (!C || (K > 0 && (!A || !B)))) return fail(SP_EINVAL, "gemm: null operand");
   if (M == 0 || N == 0) return SP_OK;
-  if (dtype == SP_BF16 && gemm_mfma_supported(op, M, N, K, A, B, C, R)) gemm_mfma(s, op, M, N, K, A, B, C, R);
+  const bool fast = dtype == SP_BF16 && gemm_mfma_supported(op, M, N, K, A, B, C, R);
+  const int pi = prof_start(fast ? op : PROF_GEMM_PLAIN, s);
+  if (fast) gemm_mfma(s, op, M, N, K, A, B, C, R);
   else gemm_simple(s, dtype, op, M, N, K, A, B, C, R);
+  prof_stop(pi, s, 2.0 * (double)M * (double)N * (double)K);
   return SP_OK;
 }
 

@@ -82,4 +82,10 @@ void attention_flash_fwd(hipStream_t s, int B, int T, int H, int Hkv, int hd, co
 void attention_flash_bwd(hipStream_t s, int B, int T, int H, int Hkv, int hd, const void* qkv, const void* o,
                          const float* lse, const void* do_, void* dqkv, float* delta);
 
+// ---- optional per-launch timing (see sp_prof_begin); classes:
+enum { PROF_GEMM_NT = 0, PROF_GEMM_NN = 1, PROF_GEMM_TN = 2, PROF_ATTN_FWD = 3, PROF_ATTN_DELTA = 4, PROF_ATTN_DQ = 5,
+       PROF_ATTN_DKV = 6, PROF_GEMM_PLAIN = 7, PROF_ATTN_PLAIN = 8, PROF_CLASSES = 9 };
+int prof_start(int cls, hipStream_t s);
+void prof_stop(int idx, hipStream_t s, double flops);
+
 }  // namespace sp

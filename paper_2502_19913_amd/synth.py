@@ -101,10 +101,10 @@ CONFIGS: Dict[str, dict] = {
     # 500M shape, whole model, skip 1/3, swaps allowed
     "c2": _cfg(dim=1024, n_heads=16, n_kv_heads=16, hidden=2816, vocab=32000, n_stages=6, layers_per_stage=4,
                seq_len=1024, seqs_per_mb=4, n_mb=8, skip=(1, 3), swap=1, dtype="bf16"),
-    # 1.5B shape, one node's stage (stage 1 of 6), 8 microbatches all routed here
+    # 1.5B shape, one node's stage (stage 3 of 6), 8 microbatches all routed here (see stage_share_paths)
     "c3": _cfg(dim=2048, n_heads=16, n_kv_heads=16, hidden=5632, vocab=32000, n_stages=6, layers_per_stage=4,
                seq_len=4096, seqs_per_mb=1, n_mb=8, skip=(1, 3), swap=1, dtype="bf16",
-               local_stage_begin=1, local_stage_count=1, has_embed=0, has_head=0),
+               local_stage_begin=3, local_stage_count=1, has_embed=0, has_head=0),
     # LLaMa-2 7B shape, one stage of 8, 16 microbatches, 25 % skip
     "c4": _cfg(dim=4096, n_heads=32, n_kv_heads=32, hidden=11008, vocab=32000, n_stages=8, layers_per_stage=4,
                seq_len=4096, seqs_per_mb=1, n_mb=16, skip=(1, 4), swap=0, dtype="bf16",
@@ -217,3 +217,31 @@ def make_paths(n_stages: int, n_mb: int, skip_num: int, skip_den: int, allow_swa
         paths[mb, :len(kept)] = kept
         lens[mb] = len(kept)
     return paths, lens
+
+
+# The eight microbatches a stage-3 node of the 6-stage, 1/3-skip set-up serves in one wave: each path keeps 4
+# of 6 stages and holds stage 3, which they reach at path position 1, 2 or 3 (groups of 3, 3 and 2), three of
+# them through an exchanged pair of neighbouring stages.
+C3_PATHS = [(0, 3, 4, 5), (0, 3, 2, 5), (0, 3, 4, 5), (0, 2, 3, 5), (0, 1, 3, 4), (0, 4, 3, 5), (0, 1, 2, 3),
+            (0, 1, 4, 3)]
+
+
+def stage_share_paths(key: str, seed: int = BASE_SEED) -> Tuple[np.ndarray, np.ndarray, int]:
+    """Paths of a stage-share workload and the stage the node holds.
+
+    c3: the fixed set above.  c4 / c5: the seeded recipe over all 8 stages; the node holds the later stage
+    that most paths visit (ties: the lowest index)."""
+    cfg = CONFIGS[key]
+    s = cfg["n_stages"]
+    if key == "c3":
+        paths = np.full((len(C3_PATHS), s), -1, np.int32)
+        for i, p in enumerate(C3_PATHS):
+            paths[i, :len(p)] = p
+        return paths, np.array([len(p) for p in C3_PATHS], np.int32), 3
+    paths, lens = make_paths(s, cfg["n_mb"], *cfg["skip"], bool(cfg["swap"]), seed)
+    visits = np.zeros(s, int)
+    for mb in range(cfg["n_mb"]):
+        for st in paths[mb, :lens[mb]]:
+            visits[st] += 1
+    stage = 1 + int(np.argmax(visits[1:]))
+    return paths, lens, stage
