@@ -1,19 +1,29 @@
 // bf16 matrix products on the CDNA4 matrix cores (v_mfma_f32_32x32x16_bf16), float accumulation.
 //
 // One workgroup of 8 wavefronts owns a 256x256 tile of the output and walks the reduction
-// dimension in steps of 64.  Both operand tiles live in LDS as [row][k] with rows padded to 144
-// bytes, double buffered (147 KB of the CU's 160 KB): a wavefront reads its MFMA fragments with one
-// 16-byte LDS load per lane (8 consecutive k for one row), conflict free thanks to the padding.
-// The next step's tiles are fetched from global memory into registers before the current step's
-// MFMAs are issued and written to the other LDS buffer afterwards, so one barrier per step suffices.
+// dimension in steps of 64.  Operand tiles are staged global -> registers -> LDS with buffer loads
+// (the hardware range check returns zero past the end of an operand, so ragged edges need no
+// branches) two steps ahead of the MFMAs, into two LDS buffers (147 KB of the CU's 160 KB); one
+// barrier per step.
 //
-// Operand layouts:
-//   op 0  C[M,N]  = A[M,K] B[N,K]^T (+R)   both operands k-contiguous: 16-byte chunks go straight to LDS
-//   op 1  C[M,N]  = A[M,K] B[K,N]          B is k-strided: 4x8 blocks are transposed in registers
-//   op 2  C[M,N] += A[K,M]^T B[K,N]        both k-strided; float output, optional split of K with
-//                                          atomic accumulation so that few output tiles still fill the chip
-// Wavefront layout inside the tile: 2 (M) x 4 (N), each wavefront 128x64 = 4x2 MFMA tiles, 128
-// accumulator registers.  Workgroup ids are regrouped so that the ids that land on one XCD (id mod 8)
+// LDS layouts, chosen so that every fragment read is conflict free and every global access is a
+// full 16-byte chunk of a contiguous run:
+//   k-contiguous operand (memory [row][k]): LDS [row][64 k] padded to 144 B; a lane's MFMA fragment
+//     (8 consecutive k of one row) is one ds_read_b128.
+//   k-strided operand (memory [k][x]):      LDS [64 k][256 x] padded to 576 B, copied as is; the
+//     fragment is gathered by two ds_read_b64_tr_b16 (the LDS transpose read: within 16 lanes,
+//     lane i receives element i%4 of the 8-byte pieces addressed by lanes i/4, i/4+4, i/4+8, i/4+12).
+//
+//   op 0  C[M,N]  = A[M,K] B[N,K]^T (+R)   A, B k-contiguous
+//   op 1  C[M,N]  = A[M,K] B[K,N]          B k-strided
+//   op 2  C[M,N] += A[K,M]^T B[K,N]        both k-strided; float output; K may be split over
+//                                          workgroups (atomic accumulation) when the output has few tiles
+//
+// For bf16 outputs the MFMA is issued with the tile of B as its row operand and the tile of A as its
+// column operand, so a lane's accumulator holds 4 consecutive output columns of one output row; they go
+// through LDS ([256][256] padded to 528 B) and leave as coalesced 16-byte stores, the optional
+// added matrix R is read the same way.  Wavefront layout inside the tile: 2 (M) x 4 (N), each
+// wavefront 128x64.  Workgroup ids are regrouped so that the ids that land on one XCD (id mod 8)
 // cover neighbouring tiles and share operand panels in that XCD's L2.
 #include "devutil.h"
 #include "internal.h"
@@ -23,74 +33,98 @@ namespace sp {
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
 
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int kThreads = 512;
-constexpr int kRowBytes = 144;                   // 64 bf16 + 16 bytes of padding
-constexpr int kTileBytes = 256 * kRowBytes;      // one operand tile
-constexpr int kLdsBytes = 4 * kTileBytes;        // A and B, two buffers
+constexpr int kRowBytes = 144;                  // k-contiguous tile: 64 bf16 + 16 bytes of padding per row
+constexpr int kKRowBytes = 576;                 // k-strided tile: 256 bf16 + 64 bytes of padding per k
+constexpr int kTileBytes = 256 * kRowBytes;     // = 64 * kKRowBytes
+constexpr int kLdsBytes = 4 * kTileBytes;       // A and B, two buffers
+constexpr int kCRowBytes = 528;                 // output staging: 256 bf16 + 16 bytes
+static_assert(64 * kKRowBytes == kTileBytes, "both tile layouts have the same footprint");
+static_assert(256 * kCRowBytes <= kLdsBytes, "output staging fits in the operand buffers");
 
-__device__ __forceinline__ uint4 zero4() { return make_uint4(0u, 0u, 0u, 0u); }
-
-// ---- global -> registers ------------------------------------------------------------------------
-// k-contiguous operand X[rows][ld]: tile rows [r0, r0+256), k in [k0, k0+64).  Thread t takes the
-// 16-byte chunks t, t+512, t+1024, t+1536 of the 2048 in the tile (chunk = row*8 + kchunk).
-__device__ __forceinline__ void load_kcontig(const bf16* __restrict__ X, int64_t ld, int rows, int r0, int k0, int kend,
-                                             int tid, uint4 (&reg)[4]) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int c = tid + kThreads * i;
-    const int row = c >> 3, kc = c & 7;
-    const int gr = min(r0 + row, rows - 1);     // rows past the edge re-read the last row; never stored
-    const int gk = k0 + kc * 8;
-    reg[i] = gk < kend ? *reinterpret_cast<const uint4*>(X + (int64_t)gr * ld + gk) : zero4();
-  }
+__device__ __forceinline__ rsrc_t make_rsrc(const void* p, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
 }
-__device__ __forceinline__ void store_kcontig(char* s, int tid, const uint4 (&reg)[4]) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int c = tid + kThreads * i;
-    *reinterpret_cast<uint4*>(s + (c >> 3) * kRowBytes + (c & 7) * 16) = reg[i];
-  }
+// 16 bytes at byte offset voff; zero if voff is at or past the end of the buffer
+__device__ __forceinline__ uint4 bload(rsrc_t rsrc, uint32_t voff) {
+  i32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)voff, 0, 0);
+  return make_uint4((uint32_t)v[0], (uint32_t)v[1], (uint32_t)v[2], (uint32_t)v[3]);
 }
 
-// k-strided operand X[k][ld] (the tile's "row" index x runs along memory): x in [x0, x0+256),
-// k in [k0, k0+64).  Thread t takes the 4(k) x 8(x) block (kquad = t & 15, xblock = t >> 4).
-__device__ __forceinline__ void load_kstrided(const bf16* __restrict__ X, int64_t ld, int xdim, int x0, int k0, int kend,
-                                              int tid, uint4 (&reg)[4]) {
-  const int kq = tid & 15, xb = tid >> 4;
-  const int gx = x0 + xb * 8;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int gk = k0 + kq * 4 + i;
-    reg[i] = (gk < kend && gx < xdim) ? *reinterpret_cast<const uint4*>(X + (int64_t)gk * ld + gx) : zero4();
-  }
-}
-// transposes the 4x8 block and writes 8 rows of 4 consecutive k (8 bytes each)
-__device__ __forceinline__ void store_kstrided(char* s, int tid, const uint4 (&reg)[4]) {
-  const int kq = tid & 15, xb = tid >> 4;
-  const uint32_t w[4][4] = {{reg[0].x, reg[0].y, reg[0].z, reg[0].w}, {reg[1].x, reg[1].y, reg[1].z, reg[1].w},
-                            {reg[2].x, reg[2].y, reg[2].z, reg[2].w}, {reg[3].x, reg[3].y, reg[3].z, reg[3].w}};
-#pragma unroll
-  for (int c = 0; c < 8; ++c) {
-    const int j = c >> 1;
-    uint2 o;
-    if (c & 1) {
-      o.x = (w[0][j] >> 16) | (w[1][j] & 0xffff0000u);
-      o.y = (w[2][j] >> 16) | (w[3][j] & 0xffff0000u);
+// One operand's share of the staging for one thread: 4 chunks of 16 bytes.
+template <bool KSTRIDED>
+struct Operand {
+  rsrc_t rsrc;
+  uint32_t voff0;      // byte offset of this thread's chunk 0 at k = 0
+  uint32_t chunk_step; // distance between the thread's consecutive chunks
+  uint32_t k_step;     // byte distance of one k element
+  int kc8;             // k-contiguous: first k of the thread's chunk inside a step
+  int lds_off;         // byte offset of chunk 0 in the LDS tile
+  // ld: leading dimension (elements); origin: first tile row (k-contiguous) or first x (k-strided)
+  __device__ __forceinline__ void init(const bf16* X, uint32_t bytes, int ld, int origin, int tid) {
+    rsrc = make_rsrc(X, bytes);
+    if (KSTRIDED) {
+      const int krow = tid >> 5, xc = tid & 31;          // chunk c = tid + 512 i: k row c / 32, x chunk c % 32
+      voff0 = ((uint32_t)krow * ld + origin + xc * 8) * 2u;
+      chunk_step = 16u * ld * 2u;
+      k_step = (uint32_t)ld * 2u;
+      kc8 = 0;
+      lds_off = krow * kKRowBytes + xc * 16;
     } else {
-      o.x = (w[0][j] & 0xffffu) | (w[1][j] << 16);
-      o.y = (w[2][j] & 0xffffu) | (w[3][j] << 16);
+      const int row = tid >> 3, kc = tid & 7;            // chunk c = tid + 512 i: row c / 8, k chunk c % 8
+      voff0 = ((uint32_t)(origin + row) * ld + kc * 8) * 2u;
+      chunk_step = 64u * ld * 2u;
+      k_step = 2u;
+      kc8 = kc * 8;
+      lds_off = row * kRowBytes + kc * 16;
     }
-    *reinterpret_cast<uint2*>(s + (xb * 8 + c) * kRowBytes + kq * 8) = o;
+  }
+  // KMASK (k-contiguous only): chunks whose k is at or past kend read as zero
+  template <bool KMASK>
+  __device__ __forceinline__ void load(int k0, int kend, uint4 (&reg)[4]) const {
+    const uint32_t base = voff0 + (uint32_t)k0 * k_step;
+    const bool dead = KMASK && !KSTRIDED && (k0 + kc8 >= kend);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) reg[i] = bload(rsrc, dead ? 0xffffffffu : base + i * chunk_step);
+  }
+  __device__ __forceinline__ void store(char* tile, const uint4 (&reg)[4]) const {
+    constexpr int step = KSTRIDED ? 16 * kKRowBytes : 64 * kRowBytes;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4*>(tile + lds_off + i * step) = reg[i];
+  }
+};
+
+// MFMA fragment of tile row `row` (0..255) for k-step ks (16 k): 8 consecutive k, starting at
+// ks*16 + (lane/32)*8, of that row.
+template <bool KSTRIDED>
+__device__ __forceinline__ bf16x8 read_frag(const char* tile, int row_base, int ks, int lane) {
+  if (!KSTRIDED) {
+    return *reinterpret_cast<const bf16x8*>(tile + (row_base + (lane & 31)) * kRowBytes + ks * 32 + (lane >> 5) * 16);
+  } else {
+    // group of 16 lanes = 16 consecutive x; lane s of the group addresses k row s/4, x piece s%4
+    const int g16 = (lane >> 4) & 1, hh = lane >> 5, s = lane & 15;
+    const char* p = tile + (ks * 16 + hh * 8 + (s >> 2)) * kKRowBytes + (row_base + g16 * 16 + (s & 3) * 4) * 2;
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * kKRowBytes));
+    typedef __attribute__((ext_vector_type(8))) short s16x8;
+    s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8, v);
   }
 }
 
-template <int OP>
+template <int OP, bool KMASK>
 __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ B,
                                                         void* __restrict__ Cv, const bf16* __restrict__ Rr, int M,
                                                         int N, int K, int tiles_m, int tiles_n, int ksplit) {
+  constexpr bool AS = OP == 2, BS = OP != 0;   // which operands are k-strided
   __shared__ __attribute__((aligned(16))) char smem[kLdsBytes];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 2, wn = wave & 3;
@@ -108,79 +142,140 @@ __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__
   const int tm = in_band / band_w, tn = band * kBand + in_band % band_w;
   const int m0 = tm * BM, n0 = tn * BN;
   const int kb = blockIdx.y * ksplit, kend = min(K, kb + ksplit);
+  const int nk = (kend - kb + BK - 1) / BK;
 
+  Operand<AS> opa;
+  Operand<BS> opb;
+  opa.init(A, (uint32_t)((size_t)M * K * 2), AS ? M : K, m0, tid);
+  opb.init(B, (uint32_t)((size_t)N * K * 2), BS ? N : K, n0, tid);
+
+  // acc[j][i]: MFMA rows = 32 output columns n (i of 2), MFMA columns = 32 output rows m (j of 4)
   f32x16 acc[4][2];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int j = 0; j < 4; ++j)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+      for (int r = 0; r < 16; ++r) acc[j][i][r] = 0.f;
 
-  uint4 ra[4], rb[4];
-  auto load_tiles = [&](int k0) {
-    if (OP == 2) load_kstrided(A, M, M, m0, k0, kend, tid, ra); else load_kcontig(A, K, M, m0, k0, kend, tid, ra);
-    if (OP == 0) load_kcontig(B, K, N, n0, k0, kend, tid, rb); else load_kstrided(B, N, N, n0, k0, kend, tid, rb);
-  };
-  auto store_tiles = [&](int buf) {
-    char* sa = smem + buf * 2 * kTileBytes;
-    char* sb = sa + kTileBytes;
-    if (OP == 2) store_kstrided(sa, tid, ra); else store_kcontig(sa, tid, ra);
-    if (OP == 0) store_kcontig(sb, tid, rb); else store_kstrided(sb, tid, rb);
-  };
-
-  const int nk = (kend - kb + BK - 1) / BK;
-  if (nk > 0) {
-    load_tiles(kb);
-    store_tiles(0);
-  }
-  __syncthreads();
-  const int frag_off = (lane & 31) * kRowBytes + (lane >> 5) * 16;
-  for (int kt = 0; kt < nk; ++kt) {
-    const bool more = kt + 1 < nk;
-    if (more) load_tiles(kb + (kt + 1) * BK);
-    const char* sa = smem + (kt & 1) * 2 * kTileBytes + wm * 128 * kRowBytes + frag_off;
-    const char* sb = smem + (kt & 1) * 2 * kTileBytes + kTileBytes + wn * 64 * kRowBytes + frag_off;
+  uint4 ra[2][4], rb[2][4];
+  auto compute = [&](const char* base) {
+    const char* ta = base;
+    const char* tb = base + kTileBytes;
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 af[4], bf[2];
+      bf16x8 fa[4], fb[2];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) af[i] = *reinterpret_cast<const bf16x8*>(sa + i * 32 * kRowBytes + ks * 32);
+      for (int j = 0; j < 4; ++j) fa[j] = read_frag<AS>(ta, wm * 128 + j * 32, ks, lane);
 #pragma unroll
-      for (int j = 0; j < 2; ++j) bf[j] = *reinterpret_cast<const bf16x8*>(sb + j * 32 * kRowBytes + ks * 32);
+      for (int i = 0; i < 2; ++i) fb[i] = read_frag<BS>(tb, wn * 64 + i * 32, ks, lane);
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+      for (int j = 0; j < 4; ++j)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+        for (int i = 0; i < 2; ++i)
+          acc[j][i] = OP == 2 ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[j], fb[i], acc[j][i], 0, 0, 0)
+                              : __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[i], fa[j], acc[j][i], 0, 0, 0);
     }
-    if (more) store_tiles((kt + 1) & 1);
+  };
+  auto gload = [&](int t, uint4 (&xa)[4], uint4 (&xb)[4]) {
+    opa.template load<KMASK>(kb + t * BK, kend, xa);
+    opb.template load<KMASK>(kb + t * BK, kend, xb);
+  };
+  auto sstore = [&](int t, const uint4 (&xa)[4], const uint4 (&xb)[4]) {
+    char* d = smem + (t & 1) * 2 * kTileBytes;
+    opa.store(d, xa);
+    opb.store(d + kTileBytes, xb);
+  };
+
+  // tile t of the reduction waits in register set t & 1 until it is written to LDS buffer t & 1
+  if (nk > 0) {
+    gload(0, ra[0], rb[0]);
+    if (nk > 1) gload(1, ra[1], rb[1]);
+    sstore(0, ra[0], rb[0]);
+  }
+  __syncthreads();
+  int kt = 0;
+  for (; kt + 3 < nk; kt += 2) {   // steady state: no conditionals, so outstanding loads can be counted
+    gload(kt + 2, ra[0], rb[0]);
+    compute(smem);
+    sstore(kt + 1, ra[1], rb[1]);
+    __syncthreads();
+    gload(kt + 3, ra[1], rb[1]);
+    compute(smem + 2 * kTileBytes);
+    sstore(kt + 2, ra[0], rb[0]);
+    __syncthreads();
+  }
+  for (; kt < nk; ++kt) {          // the last (up to three) steps
+    const bool odd = kt & 1;
+    if (kt + 2 < nk) { if (odd) gload(kt + 2, ra[1], rb[1]); else gload(kt + 2, ra[0], rb[0]); }
+    compute(smem + (kt & 1) * 2 * kTileBytes);
+    if (kt + 1 < nk) { if (odd) sstore(kt + 1, ra[0], rb[0]); else sstore(kt + 1, ra[1], rb[1]); }
     __syncthreads();
   }
 
-  // ---- epilogue.  Accumulator r of lane l sits at row (r/4)*8 + (l/32)*4 + r%4, column l%32 of its 32x32 tile.
-  const bool atomic = gridDim.y > 1;
+  // ---- epilogue.  Accumulator r of lane l: output row m = lane%32, output column n = (r/4)*8 + (l/32)*4 + r%4
+  // of its 32x32 tile, i.e. 4 consecutive columns per group of 4 registers.
+  const int lm = lane & 31, hh = lane >> 5;
+  if (OP == 2) {
+    // float output, accumulated in place.  Here the tile of A is the MFMA's row operand: accumulator r of
+    // lane l is output row (r/4)*8 + (l/32)*4 + r%4, column l%32, so a wavefront's access covers 128
+    // contiguous bytes of two rows (coalesced atomics when K is split).
+    float* C = reinterpret_cast<float*>(Cv);
+    const bool atomic = gridDim.y > 1;
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int col = n0 + wn * 64 + j * 32 + (lane & 31);
+      for (int i = 0; i < 2; ++i) {
+        const int col = n0 + wn * 64 + i * 32 + lm;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = m0 + wm * 128 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-        if (row < M && col < N) {
-          const int64_t at = (int64_t)row * N + col;
-          if (OP == 2) {
-            float* C = reinterpret_cast<float*>(Cv);
-            if (atomic) unsafeAtomicAdd(C + at, acc[i][j][r]); else C[at] += acc[i][j][r];
-          } else {
-            bf16* C = reinterpret_cast<bf16*>(Cv);
-            float v = acc[i][j][r];
-            if (OP == 0 && Rr) v += (float)Rr[at];
-            C[at] = (bf16)v;
+        for (int r = 0; r < 16; ++r) {
+          const int row = m0 + wm * 128 + j * 32 + (r >> 2) * 8 + hh * 4 + (r & 3);
+          if (row < M && col < N) {
+            float* p = C + (int64_t)row * N + col;
+            if (atomic) unsafeAtomicAdd(p, acc[j][i][r]); else *p += acc[j][i][r];
           }
         }
       }
+  } else {
+    // all wavefronts are past the last barrier of the loop: the operand buffers are free
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          uint2 w;
+          w.x = pack_bf16(acc[j][i][4 * g], acc[j][i][4 * g + 1]);
+          w.y = pack_bf16(acc[j][i][4 * g + 2], acc[j][i][4 * g + 3]);
+          *reinterpret_cast<uint2*>(smem + (wm * 128 + j * 32 + lm) * kCRowBytes + (wn * 64 + i * 32 + g * 8 + hh * 4) * 2) = w;
+        }
+    __syncthreads();
+    bf16* C = reinterpret_cast<bf16*>(Cv);
+    const bool add = OP == 0 && Rr != nullptr;
+#pragma unroll 4
+    for (int it = 0; it < 16; ++it) {
+      const int c = tid + kThreads * it;
+      const int row = c >> 5, nc = c & 31;
+      const int grow = m0 + row, gcol = n0 + nc * 8;
+      if (grow < M && gcol < N) {   // N is a multiple of 8: a chunk is inside or outside as a whole
+        uint4 v = *reinterpret_cast<const uint4*>(smem + row * kCRowBytes + nc * 16);
+        const int64_t at = (int64_t)grow * N + gcol;
+        if (add) {
+          // the sum is formed in float from the accumulator's bf16 rounding; one more rounding on the way out
+          float x[8], y[8];
+          const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) { x[2 * e] = bf16_bits_to_float(wv[e] & 0xffffu); x[2 * e + 1] = bf16_bits_to_float(wv[e] >> 16); }
+          load8(Rr + at, y);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) x[e] += y[e];
+          store8(C + at, x);
+        } else {
+          *reinterpret_cast<uint4*>(C + at) = v;
+        }
+      }
     }
+  }
 }
 
 inline bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
@@ -189,13 +284,16 @@ inline bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
 bool gemm_mfma_supported(int op, int64_t M, int64_t N, int64_t K, const void* A, const void* B, const void* C,
                          const void* R) {
-  if (M < 1 || N < 1 || K < 1 || M > (1 << 30) || N > (1 << 30) || K > (1 << 30)) return false;
+  if (M < 1 || N < 1 || K < 1) return false;
+  // buffer descriptors address up to 4 GiB per operand with 32-bit offsets
+  if (M * K * 2 >= ((int64_t)1 << 32) || N * K * 2 >= ((int64_t)1 << 32)) return false;
   if (!al16(A) || !al16(B) || !al16(C) || (R && !al16(R))) return false;
   if (((M + BM - 1) / BM) * ((N + BN - 1) / BN) > (1 << 24)) return false;
+  if (N % 8) return false;                      // 16-byte output chunks
   switch (op) {
     case 0: return K % 8 == 0;
-    case 1: return K % 8 == 0 && N % 8 == 0;
-    case 2: return M % 8 == 0 && N % 8 == 0;
+    case 1: return K % 8 == 0;
+    case 2: return M % 8 == 0;
   }
   return false;
 }
@@ -217,12 +315,13 @@ void gemm_mfma(hipStream_t s, int op, int64_t M, int64_t N, int64_t K, const voi
   const bf16* a = (const bf16*)A;
   const bf16* b = (const bf16*)B;
   const bf16* r = (const bf16*)R;
-  if (op == 0)
-    hipLaunchKernelGGL(k_gemm_mfma<0>, grid, dim3(kThreads), 0, s, a, b, C, r, (int)M, (int)N, (int)K, tm, tn, ksplit);
-  else if (op == 1)
-    hipLaunchKernelGGL(k_gemm_mfma<1>, grid, dim3(kThreads), 0, s, a, b, C, r, (int)M, (int)N, (int)K, tm, tn, ksplit);
-  else
-    hipLaunchKernelGGL(k_gemm_mfma<2>, grid, dim3(kThreads), 0, s, a, b, C, r, (int)M, (int)N, (int)K, tm, tn, ksplit);
+  const bool kmask = K % BK != 0;
+#define SP_LAUNCH(OP, KM) \
+  hipLaunchKernelGGL((k_gemm_mfma<OP, KM>), grid, dim3(kThreads), 0, s, a, b, C, r, (int)M, (int)N, (int)K, tm, tn, ksplit)
+  if (op == 0) { if (kmask) SP_LAUNCH(0, true); else SP_LAUNCH(0, false); }
+  else if (op == 1) { if (kmask) SP_LAUNCH(1, true); else SP_LAUNCH(1, false); }
+  else SP_LAUNCH(2, false);
+#undef SP_LAUNCH
 }
 
 }  // namespace sp
