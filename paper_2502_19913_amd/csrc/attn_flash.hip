@@ -10,7 +10,8 @@
 // per-lane scalars), a key in the dK/dV kernel (the gradients a wavefront owns).  The
 // accumulator of one MFMA then serves directly as the k-operand of the next (P for P V, dS for
 // dS K, ...) after rounding to bf16, with the 16 k-slots of the instruction assigned to rows in
-// the accumulator's own order; the LDS-side operand is read in the matching order.
+// the accumulator's own order; the LDS-side operand is gathered in the matching order by the LDS
+// transpose read, so every tile sits in LDS exactly as it sits in memory.
 //
 // Layout: qkv rows of (H + 2*Hkv)*hd = queries | keys | values; o rows of H*hd; lse, delta [B][H][T].
 #include "devutil.h"
@@ -22,6 +23,7 @@ namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;   // one staged 16-byte chunk (a native vector: stays in registers)
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -46,82 +48,46 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16& v, int u) {
   return o;
 }
 
-// LDS operand that pairs with pack8: row `row` of a [*][rows-contiguous] tile, the 8 entries at
-// offsets base + hh*4 + {0..3} and base + 8 + hh*4 + {0..3}   (two 8-byte reads)
-__device__ __forceinline__ bf16x8 read_slots(const char* tile, int stride_bytes, int row, int base, int hh) {
-  const char* p = tile + row * stride_bytes + (base + hh * 4) * 2;
-  uint2 a = *reinterpret_cast<const uint2*>(p);
-  uint2 b = *reinterpret_cast<const uint2*>(p + 16);
-  uint4 w = make_uint4(a.x, a.y, b.x, b.y);
-  return __builtin_bit_cast(bf16x8, w);
+// LDS operand that pairs with pack8, gathered from a row-major [row][col] tile (row stride RS bytes)
+// with the LDS transpose read: MFMA row (lane % 32) = tile column col_base + lane % 32, and the 8
+// k-slots of lane half hh = tile rows row_base + hh*4 + {0..3} and row_base + 8 + hh*4 + {0..3}.
+// (ds_read_b64_tr_b16: within 16 lanes, lane i receives element i%4 of the 8-byte pieces addressed by
+// lanes i/4, i/4+4, i/4+8, i/4+12; here piece s of a group is row s/4, columns 4*(s%4)..+3.)
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+__device__ __forceinline__ bf16x8 read_tr(const char* tile, int RS, int col_base, int row_base, int lane) {
+  const int g16 = (lane >> 4) & 1, hh = lane >> 5, sl = lane & 15;
+  const char* p = tile + (row_base + hh * 4 + (sl >> 2)) * RS + (col_base + g16 * 16 + (sl & 3) * 4) * 2;
+  typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 8 * RS));
+  const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  return __builtin_bit_cast(bf16x8, v);
 }
 
-// ---- staging of a [rows x HD] block of a row-major matrix (row stride ld elements) ----------------
-// 4 rows x 8 columns per thread.  KQ_FAST: consecutive lanes take consecutive row quads (good for
-// the transposed LDS store), else consecutive column blocks (good for the row-major store).
-template <int HD, int ROWS, bool KQ_FAST>
+// ---- staging of a [ROWS x HD] block of a row-major matrix (row stride ld elements): 16-byte chunks,
+// consecutive lanes take consecutive chunks of a row.  NCH chunks per thread (256 threads).
+template <int HD, int ROWS>
 struct Stage {
-  static constexpr int kColBlocks = HD / 8, kRowQuads = ROWS / 4;
-  static constexpr int kBlocks = kColBlocks * kRowQuads;  // may be below or above the thread count
-  uint4 reg[(kBlocks + 255) / 256][4];
-
-  __device__ __forceinline__ static void split(int blk, int& rq, int& cb) {
-    if (KQ_FAST) { rq = blk % kRowQuads; cb = blk / kRowQuads; } else { cb = blk % kColBlocks; rq = blk / kColBlocks; }
-  }
-  __device__ __forceinline__ void load(const bf16* __restrict__ X, int64_t ld, int row0, int row_max, int tid) {
+  static constexpr int kChunksPerRow = HD / 8;
+  static constexpr int kChunks = ROWS * kChunksPerRow;
+  static constexpr int NCH = (kChunks + 255) / 256;
+  __device__ __forceinline__ static void load(u32x4 (&reg)[NCH], const bf16* __restrict__ X, int64_t ld, int row0, int row_max, int tid) {
 #pragma unroll
-    for (int n = 0; n < (kBlocks + 255) / 256; ++n) {
-      const int blk = tid + 256 * n;
-      if (blk < kBlocks) {
-        int rq, cb;
-        split(blk, rq, cb);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int r = min(row0 + rq * 4 + i, row_max);
-          reg[n][i] = *reinterpret_cast<const uint4*>(X + (int64_t)r * ld + cb * 8);
-        }
+    for (int n = 0; n < NCH; ++n) {
+      const int c = tid + 256 * n;
+      if (kChunks % 256 == 0 || c < kChunks) {
+        const int r = min(row0 + c / kChunksPerRow, row_max);
+        reg[n] = *reinterpret_cast<const u32x4*>(X + (int64_t)r * ld + (c % kChunksPerRow) * 8);
       }
     }
   }
-  // tile[row][col], row stride in bytes
-  __device__ __forceinline__ void store_rows(char* tile, int stride, int tid) const {
+  __device__ __forceinline__ static void store(const u32x4 (&reg)[NCH], char* tile, int stride, int tid) {
 #pragma unroll
-    for (int n = 0; n < (kBlocks + 255) / 256; ++n) {
-      const int blk = tid + 256 * n;
-      if (blk < kBlocks) {
-        int rq, cb;
-        split(blk, rq, cb);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4*>(tile + (rq * 4 + i) * stride + cb * 16) = reg[n][i];
-      }
-    }
-  }
-  // tile[col][row], row stride in bytes
-  __device__ __forceinline__ void store_cols(char* tile, int stride, int tid) const {
-#pragma unroll
-    for (int n = 0; n < (kBlocks + 255) / 256; ++n) {
-      const int blk = tid + 256 * n;
-      if (blk < kBlocks) {
-        int rq, cb;
-        split(blk, rq, cb);
-        const uint32_t w[4][4] = {{reg[n][0].x, reg[n][0].y, reg[n][0].z, reg[n][0].w},
-                                  {reg[n][1].x, reg[n][1].y, reg[n][1].z, reg[n][1].w},
-                                  {reg[n][2].x, reg[n][2].y, reg[n][2].z, reg[n][2].w},
-                                  {reg[n][3].x, reg[n][3].y, reg[n][3].z, reg[n][3].w}};
-#pragma unroll
-        for (int c = 0; c < 8; ++c) {
-          const int j = c >> 1;
-          uint2 o;
-          if (c & 1) {
-            o.x = (w[0][j] >> 16) | (w[1][j] & 0xffff0000u);
-            o.y = (w[2][j] >> 16) | (w[3][j] & 0xffff0000u);
-          } else {
-            o.x = (w[0][j] & 0xffffu) | (w[1][j] << 16);
-            o.y = (w[2][j] & 0xffffu) | (w[3][j] << 16);
-          }
-          *reinterpret_cast<uint2*>(tile + (cb * 8 + c) * stride + rq * 8) = o;
-        }
-      }
+    for (int n = 0; n < NCH; ++n) {
+      const int c = tid + 256 * n;
+      if (kChunks % 256 == 0 || c < kChunks)
+        *reinterpret_cast<u32x4*>(tile + (c / kChunksPerRow) * stride + (c % kChunksPerRow) * 16) = reg[n];
     }
   }
 };
@@ -135,8 +101,8 @@ __global__ __launch_bounds__(256, 2) void k_flash_fwd(const bf16* __restrict__ q
                                                       float* __restrict__ lse, int T, int H, int Hkv, float scale_log2) {
   constexpr int BQ = 128, BKV = 64;
   constexpr int KS = HD * 2 + 16;   // K tile row stride (bytes): [key][hd]
-  constexpr int VS = BKV * 2 + 8;   // V^T tile row stride (bytes): [hd][key]
-  constexpr int kKTile = BKV * KS, kVTile = HD * VS;
+  constexpr int VS = HD * 2 + 64;   // V tile row stride (bytes): [key][hd], read through the transpose read
+  constexpr int kKTile = BKV * KS, kVTile = BKV * VS;
   __shared__ __attribute__((aligned(16))) char smem[2 * (kKTile + kVTile)];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lq = lane & 31, hh = lane >> 5;
   const int qb = gridDim.x - 1 - blockIdx.x, a = blockIdx.y, b = blockIdx.z;
@@ -160,77 +126,101 @@ __global__ __launch_bounds__(256, 2) void k_flash_fwd(const bf16* __restrict__ q
 
   const int kv_end = min(T, q0 + BQ);
   const int ntiles = (kv_end + BKV - 1) / BKV;
-  Stage<HD, BKV, false> sk;
-  Stage<HD, BKV, true> sv;
-  sk.load(Kp, ld, 0, T - 1, tid);
-  sv.load(Vp, ld, 0, T - 1, tid);
-  sk.store_rows(smem, KS, tid);
-  sv.store_cols(smem + kKTile, VS, tid);
+  typedef Stage<HD, BKV> ST;
+  u32x4 rk[ST::NCH], rv[ST::NCH];
+  ST::load(rk, Kp, ld, 0, T - 1, tid);
+  ST::load(rv, Vp, ld, 0, T - 1, tid);
+  ST::store(rk, smem, KS, tid);
+  ST::store(rv, smem + kKTile, VS, tid);
   __syncthreads();
   for (int kt = 0; kt < ntiles; ++kt) {
     const int k0 = kt * BKV;
     const bool more = kt + 1 < ntiles;
-    if (more) {
-      sk.load(Kp, ld, k0 + BKV, T - 1, tid);
-      sv.load(Vp, ld, k0 + BKV, T - 1, tid);
-    }
+    if (more) ST::load(rk, Kp, ld, k0 + BKV, T - 1, tid);
     const char* ks = smem + (kt & 1) * (kKTile + kVTile);
     const char* vs = ks + kKTile;
     if (k0 <= qw0 + 31) {  // the tile holds a key some query of this wavefront may see
-      f32x16 st[2];
+      // S^T = K Q^T on two independent accumulators (32 keys each); the K fragments of the next two
+      // k-steps are fetched while the MFMAs of the current two run
+      f32x16 st[2] = {zero16(), zero16()};
+      bf16x8 fb[2][4];
+      const char* kr = ks + lq * KS + hh * 16;
+      auto ldk = [&](int g, bf16x8 (&f)[4]) {
+        f[0] = *reinterpret_cast<const bf16x8*>(kr + (2 * g) * 32);
+        f[1] = *reinterpret_cast<const bf16x8*>(kr + 32 * KS + (2 * g) * 32);
+        f[2] = *reinterpret_cast<const bf16x8*>(kr + (2 * g + 1) * 32);
+        f[3] = *reinterpret_cast<const bf16x8*>(kr + 32 * KS + (2 * g + 1) * 32);
+      };
+      auto ldv = [&](int tu, bf16x8 (&f)[4]) {
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        st[t] = zero16();
-        const char* kr = ks + (t * 32 + lq) * KS + hh * 16;
+        for (int c = 0; c < HD / 32; ++c) f[c] = read_tr(vs, VS, c * 32, (tu >> 1) * 32 + 16 * (tu & 1), lane);
+      };
+      ldk(0, fb[0]);
 #pragma unroll
-        for (int kk = 0; kk < HD / 16; ++kk) st[t] = mfma(*reinterpret_cast<const bf16x8*>(kr + kk * 32), qf[kk], st[t]);
+      for (int g = 0; g < HD / 32; ++g) {
+        if (g + 1 < HD / 32) ldk(g + 1, fb[(g + 1) & 1]);
+        __builtin_amdgcn_sched_barrier(0);
+        st[0] = mfma(fb[g & 1][0], qf[2 * g], st[0]);
+        st[1] = mfma(fb[g & 1][1], qf[2 * g], st[1]);
+        st[0] = mfma(fb[g & 1][2], qf[2 * g + 1], st[0]);
+        st[1] = mfma(fb[g & 1][3], qf[2 * g + 1], st[1]);
+        __builtin_amdgcn_sched_barrier(0);
       }
+      if (more) ST::load(rv, Vp, ld, k0 + BKV, T - 1, tid);   // next V tile: in flight during softmax and P V
+      ldv(0, fb[0]);  // first V fragments: their latency hides behind the softmax arithmetic
+      __builtin_amdgcn_sched_barrier(0);
       const bool mask = k0 + BKV - 1 > qw0;
       float mx = -INFINITY;
+      if (mask) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int key = k0 + t * 32 + (r >> 2) * 8 + hh * 4 + (r & 3);
+            if (key > q) st[t][r] = -INFINITY;
+          }
+      }
 #pragma unroll
       for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float s = st[t][r] * scale_log2;
-          if (mask) {
-            const int key = k0 + t * 32 + (r >> 2) * 8 + hh * 4 + (r & 3);
-            if (key > q) s = -INFINITY;
-          }
-          st[t][r] = s;
-          mx = fmaxf(mx, s);
-        }
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m_i, mx);           // finite: tile 0 holds key 0, visible to every query
-      const float alpha = exp2f(m_i - m_new);
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, st[t][r]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32)) * scale_log2;
+      // the running maximum only moves when it is exceeded by more than 2^8: probabilities stay below 256,
+      // exact after the final division, and the accumulator is rescaled rarely
+      const float m_new = mx > m_i + 8.0f ? mx : m_i;   // first tile: m_i = -inf, so m_new = mx (finite: key 0)
+      const float alpha = __builtin_amdgcn_exp2f(m_i - m_new);
       float rs = 0.f;
 #pragma unroll
       for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const float p = exp2f(st[t][r] - m_new);
-          st[t][r] = p;
-          rs += p;
+          const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(st[t][r], scale_log2, -m_new));
+          st[t][r] = pv;
+          rs += pv;
         }
       l_i = l_i * alpha + rs;
       m_i = m_new;
+      if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
-      for (int c = 0; c < HD / 32; ++c)
+        for (int c = 0; c < HD / 32; ++c)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[c][r] *= alpha;
+          for (int r = 0; r < 16; ++r) oacc[c][r] *= alpha;
+      }
 #pragma unroll
-      for (int t = 0; t < 2; ++t)
+      for (int tu = 0; tu < 4; ++tu) {
+        if (tu + 1 < 4) ldv(tu + 1, fb[(tu + 1) & 1]);
+        __builtin_amdgcn_sched_barrier(0);
+        const bf16x8 pf = pack8(st[tu >> 1], tu & 1);
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          const bf16x8 pf = pack8(st[t], u);
-#pragma unroll
-          for (int c = 0; c < HD / 32; ++c)
-            oacc[c] = mfma(read_slots(vs, VS, c * 32 + lq, t * 32 + 16 * u, hh), pf, oacc[c]);
-        }
+        for (int c = 0; c < HD / 32; ++c) oacc[c] = mfma(fb[tu & 1][c], pf, oacc[c]);
+      }
+    } else if (more) {
+      ST::load(rv, Vp, ld, k0 + BKV, T - 1, tid);
     }
     if (more) {
       char* nk = smem + ((kt + 1) & 1) * (kKTile + kVTile);
-      sk.store_rows(nk, KS, tid);
-      sv.store_cols(nk + kKTile, VS, tid);
+      ST::store(rk, nk, KS, tid);
+      ST::store(rv, nk + kKTile, VS, tid);
     }
     __syncthreads();
   }
@@ -287,8 +277,8 @@ __global__ __launch_bounds__(256, 2) void k_flash_bwd_dq(const bf16* __restrict_
                                                          bf16* __restrict__ dqkv, int T, int H, int Hkv, float scale) {
   constexpr int BQ = 128, BKV = 64;
   constexpr int KS = HD * 2 + 16;   // K and V tiles [key][hd]
-  constexpr int TS = BKV * 2 + 8;   // K^T tile [hd][key]
-  constexpr int kKTile = BKV * KS, kTTile = HD * TS;
+  constexpr int TS = HD * 2 + 64;   // second copy of K, [key][hd], strided for the transpose read
+  constexpr int kKTile = BKV * KS, kTTile = BKV * TS;
   __shared__ __attribute__((aligned(16))) char smem[2 * kKTile + kTTile];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lq = lane & 31, hh = lane >> 5;
   const int qb = gridDim.x - 1 - blockIdx.x, a = blockIdx.y, b = blockIdx.z;
@@ -321,46 +311,68 @@ __global__ __launch_bounds__(256, 2) void k_flash_bwd_dq(const bf16* __restrict_
   char* kts = smem + 2 * kKTile;
   const int kv_end = min(T, q0 + BQ);
   const int ntiles = (kv_end + BKV - 1) / BKV;
-  Stage<HD, BKV, true> sk;
-  Stage<HD, BKV, false> sv;
-  sk.load(Kp, ld, 0, T - 1, tid);
-  sv.load(Vp, ld, 0, T - 1, tid);
+  typedef Stage<HD, BKV> ST;
+  u32x4 rk[ST::NCH], rv[ST::NCH];
+  ST::load(rk, Kp, ld, 0, T - 1, tid);
+  ST::load(rv, Vp, ld, 0, T - 1, tid);
   for (int kt = 0; kt < ntiles; ++kt) {
     const int k0 = kt * BKV;
-    sk.store_rows(ks, KS, tid);
-    sk.store_cols(kts, TS, tid);
-    sv.store_rows(vs, KS, tid);
+    ST::store(rk, ks, KS, tid);
+    ST::store(rk, kts, TS, tid);
+    ST::store(rv, vs, KS, tid);
     __syncthreads();
     if (kt + 1 < ntiles) {
-      sk.load(Kp, ld, k0 + BKV, T - 1, tid);
-      sv.load(Vp, ld, k0 + BKV, T - 1, tid);
+      ST::load(rk, Kp, ld, k0 + BKV, T - 1, tid);
+      ST::load(rv, Vp, ld, k0 + BKV, T - 1, tid);
     }
     if (k0 <= qw0 + 31) {
       const bool mask = k0 + BKV - 1 > qw0;
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
+        // S^T and dP^T as two independent MFMA chains; K and V fragments fetched two k-steps ahead
         f32x16 st = zero16(), dp = zero16();
+        bf16x8 fb[2][4];
         const char* kr = ks + (t * 32 + lq) * KS + hh * 16;
         const char* vr = vs + (t * 32 + lq) * KS + hh * 16;
+        auto ldkv = [&](int g, bf16x8 (&f)[4]) {
+          f[0] = *reinterpret_cast<const bf16x8*>(kr + (2 * g) * 32);
+          f[1] = *reinterpret_cast<const bf16x8*>(vr + (2 * g) * 32);
+          f[2] = *reinterpret_cast<const bf16x8*>(kr + (2 * g + 1) * 32);
+          f[3] = *reinterpret_cast<const bf16x8*>(vr + (2 * g + 1) * 32);
+        };
+        auto ldt = [&](int u, bf16x8 (&f)[4]) {
 #pragma unroll
-        for (int kk = 0; kk < HD / 16; ++kk) st = mfma(*reinterpret_cast<const bf16x8*>(kr + kk * 32), qf[kk], st);
+          for (int c = 0; c < HD / 32; ++c) f[c] = read_tr(kts, TS, c * 32, t * 32 + 16 * u, lane);
+        };
+        ldkv(0, fb[0]);
 #pragma unroll
-        for (int kk = 0; kk < HD / 16; ++kk) dp = mfma(*reinterpret_cast<const bf16x8*>(vr + kk * 32), dof[kk], dp);
+        for (int g = 0; g < HD / 32; ++g) {
+          if (g + 1 < HD / 32) ldkv(g + 1, fb[(g + 1) & 1]);
+          __builtin_amdgcn_sched_barrier(0);
+          st = mfma(fb[g & 1][0], qf[2 * g], st);
+          dp = mfma(fb[g & 1][1], dof[2 * g], dp);
+          st = mfma(fb[g & 1][2], qf[2 * g + 1], st);
+          dp = mfma(fb[g & 1][3], dof[2 * g + 1], dp);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        ldt(0, fb[0]);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          float p = exp2f(st[r] * scale_log2 - lse2);
+          float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(st[r], scale_log2, -lse2));
           if (mask) {
             const int key = k0 + t * 32 + (r >> 2) * 8 + hh * 4 + (r & 3);
-            if (key > q) p = 0.f;
+            if (key > q) pv = 0.f;
           }
-          st[r] = p * (dp[r] - dlt);
+          st[r] = pv * (dp[r] - dlt);
         }
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
+          if (u + 1 < 2) ldt(u + 1, fb[(u + 1) & 1]);
+          __builtin_amdgcn_sched_barrier(0);
           const bf16x8 dsf = pack8(st, u);
 #pragma unroll
-          for (int c = 0; c < HD / 32; ++c)
-            dq[c] = mfma(read_slots(kts, TS, c * 32 + lq, t * 32 + 16 * u, hh), dsf, dq[c]);
+          for (int c = 0; c < HD / 32; ++c) dq[c] = mfma(fb[u & 1][c], dsf, dq[c]);
         }
       }
     }
@@ -392,8 +404,8 @@ __global__ __launch_bounds__(256) void k_flash_bwd_dkv(const bf16* __restrict__ 
                                                        bf16* __restrict__ dqkv, int T, int H, int Hkv, float scale) {
   constexpr int BK = 128, BQ = 32;
   constexpr int QS = HD * 2 + 16;   // Q and dO tiles [query][hd]
-  constexpr int TS = BQ * 2 + 8;    // Q^T and dO^T tiles [hd][query]
-  constexpr int kQTile = BQ * QS, kTTile = HD * TS;
+  constexpr int TS = HD * 2 + 64;   // second copies of Q and dO, [query][hd], strided for the transpose read
+  constexpr int kQTile = BQ * QS, kTTile = BQ * TS;
   constexpr int kBuf = 2 * kQTile + 2 * kTTile + 2 * BQ * 4;
   __shared__ __attribute__((aligned(16))) char smem[2 * kBuf];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lk = lane & 31, hh = lane >> 5;
@@ -422,13 +434,14 @@ __global__ __launch_bounds__(256) void k_flash_bwd_dkv(const bf16* __restrict__ 
   const int qt0 = k0 / BQ, nqt = (T + BQ - 1) / BQ;   // query tiles that can see a key of this block
   const int per_head = nqt - qt0;
   const int steps = per_head * rep;
-  Stage<HD, BQ, true> sq, sdo;
+  typedef Stage<HD, BQ> SQ;
+  u32x4 rq[SQ::NCH], rdo[SQ::NCH];
   float st_lse = 0.f, st_dlt = 0.f;
   auto load_step = [&](int step) {
     const int a = kvh * rep + step / per_head;
     const int qs = (qt0 + step % per_head) * BQ;
-    sq.load(qkv + (int64_t)b * T * ld + a * HD, ld, qs, T - 1, tid);
-    sdo.load(dO + (int64_t)b * T * H * HD + a * HD, (int64_t)H * HD, qs, T - 1, tid);
+    SQ::load(rq, qkv + (int64_t)b * T * ld + a * HD, ld, qs, T - 1, tid);
+    SQ::load(rdo, dO + (int64_t)b * T * H * HD + a * HD, (int64_t)H * HD, qs, T - 1, tid);
     if (tid < BQ) {
       const int qi = min(qs + tid, T - 1);
       st_lse = lse[((int64_t)b * H + a) * T + qi] * kLog2e;
@@ -437,10 +450,10 @@ __global__ __launch_bounds__(256) void k_flash_bwd_dkv(const bf16* __restrict__ 
   };
   auto store_step = [&](int buf) {
     char* base = smem + buf * kBuf;
-    sq.store_rows(base, QS, tid);
-    sdo.store_rows(base + kQTile, QS, tid);
-    sq.store_cols(base + 2 * kQTile, TS, tid);
-    sdo.store_cols(base + 2 * kQTile + kTTile, TS, tid);
+    SQ::store(rq, base, QS, tid);
+    SQ::store(rdo, base + kQTile, QS, tid);
+    SQ::store(rq, base + 2 * kQTile, TS, tid);
+    SQ::store(rdo, base + 2 * kQTile + kTTile, TS, tid);
     if (tid < BQ) {
       reinterpret_cast<float*>(base + 2 * kQTile + 2 * kTTile)[tid] = st_lse;
       reinterpret_cast<float*>(base + 2 * kQTile + 2 * kTTile + BQ * 4)[tid] = st_dlt;
@@ -464,12 +477,33 @@ __global__ __launch_bounds__(256) void k_flash_bwd_dkv(const bf16* __restrict__ 
       const float* s_lse = reinterpret_cast<const float*>(base + 2 * kQTile + 2 * kTTile);
       const float* s_dlt = s_lse + BQ;
       f32x16 s = zero16(), dp = zero16();
+      bf16x8 fb[2][4];
       const char* qr = qsm + lk * QS + hh * 16;     // A operand: row = query lk of the tile
       const char* dr = dosm + lk * QS + hh * 16;
+      auto ldq = [&](int g, bf16x8 (&f)[4]) {
+        f[0] = *reinterpret_cast<const bf16x8*>(qr + (2 * g) * 32);
+        f[1] = *reinterpret_cast<const bf16x8*>(dr + (2 * g) * 32);
+        f[2] = *reinterpret_cast<const bf16x8*>(qr + (2 * g + 1) * 32);
+        f[3] = *reinterpret_cast<const bf16x8*>(dr + (2 * g + 1) * 32);
+      };
+      // group w of the second phase: w = 2u + (0: dO^T for dV, 1: Q^T for dK)
+      auto ldt = [&](int w, bf16x8 (&f)[4]) {
 #pragma unroll
-      for (int kk = 0; kk < HD / 16; ++kk) s = mfma(*reinterpret_cast<const bf16x8*>(qr + kk * 32), kf[kk], s);
+        for (int c = 0; c < HD / 32; ++c) f[c] = read_tr((w & 1) ? qts : dots, TS, c * 32, 16 * (w >> 1), lane);
+      };
+      ldq(0, fb[0]);
 #pragma unroll
-      for (int kk = 0; kk < HD / 16; ++kk) dp = mfma(*reinterpret_cast<const bf16x8*>(dr + kk * 32), vf[kk], dp);
+      for (int g = 0; g < HD / 32; ++g) {
+        if (g + 1 < HD / 32) ldq(g + 1, fb[(g + 1) & 1]);
+        __builtin_amdgcn_sched_barrier(0);
+        s = mfma(fb[g & 1][0], kf[2 * g], s);
+        dp = mfma(fb[g & 1][1], vf[2 * g], dp);
+        s = mfma(fb[g & 1][2], kf[2 * g + 1], s);
+        dp = mfma(fb[g & 1][3], vf[2 * g + 1], dp);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      ldt(0, fb[0]);
+      __builtin_amdgcn_sched_barrier(0);
       const bool mask = qs < kw0 + 31;
       f32x16 p;
 #pragma unroll
@@ -481,7 +515,7 @@ __global__ __launch_bounds__(256) void k_flash_bwd_dkv(const bf16* __restrict__ 
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int r = 4 * g + e;
-          float pv = exp2f(s[r] * scale_log2 - lv[e]);
+          float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], scale_log2, -lv[e]));
           if (mask && key > qs + qi + e) pv = 0.f;
           if (qs + qi + e >= T) pv = 0.f;     // rows past the end of the sequence are re-reads of row T-1
           p[r] = pv;
@@ -489,12 +523,14 @@ __global__ __launch_bounds__(256) void k_flash_bwd_dkv(const bf16* __restrict__ 
         }
       }
 #pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        const bf16x8 pf = pack8(p, u), dsf = pack8(s, u);
+      for (int w = 0; w < 4; ++w) {
+        if (w + 1 < 4) ldt(w + 1, fb[(w + 1) & 1]);
+        __builtin_amdgcn_sched_barrier(0);
+        const bf16x8 bf = pack8((w & 1) ? s : p, w >> 1);
 #pragma unroll
         for (int c = 0; c < HD / 32; ++c) {
-          dv[c] = mfma(read_slots(dots, TS, c * 32 + lk, 16 * u, hh), pf, dv[c]);
-          dk[c] = mfma(read_slots(qts, TS, c * 32 + lk, 16 * u, hh), dsf, dk[c]);
+          if (w & 1) dk[c] = mfma(fb[w & 1][c], bf, dk[c]);
+          else dv[c] = mfma(fb[w & 1][c], bf, dv[c]);
         }
       }
     }
