@@ -135,11 +135,14 @@ __global__ __launch_bounds__(256, 2) void k_flash_fwd(const bf16* __restrict__ q
   __syncthreads();
   for (int kt = 0; kt < ntiles; ++kt) {
     const int k0 = kt * BKV;
-    const bool more = kt + 1 < ntiles;
-    if (more) ST::load(rk, Kp, ld, k0 + BKV, T - 1, tid);
+    // The loop body is one straight block (no wave-dependent branch around the arithmetic): the loads of
+    // the next tile are issued here and must stay here, a whole tile of work ahead of their use.  After
+    // the last tile they re-read it, and a wavefront whose queries see no key of a tile computes zeros.
+    const int kn = min(k0 + BKV, (ntiles - 1) * BKV);
+    ST::load(rk, Kp, ld, kn, T - 1, tid);
     const char* ks = smem + (kt & 1) * (kKTile + kVTile);
     const char* vs = ks + kKTile;
-    if (k0 <= qw0 + 31) {  // the tile holds a key some query of this wavefront may see
+    {
       // S^T = K Q^T on two independent accumulators (32 keys each); the K fragments of the next two
       // k-steps are fetched while the MFMAs of the current two run
       f32x16 st[2] = {zero16(), zero16()};
@@ -166,7 +169,7 @@ __global__ __launch_bounds__(256, 2) void k_flash_fwd(const bf16* __restrict__ q
         st[1] = mfma(fb[g & 1][3], qf[2 * g + 1], st[1]);
         __builtin_amdgcn_sched_barrier(0);
       }
-      if (more) ST::load(rv, Vp, ld, k0 + BKV, T - 1, tid);   // next V tile: in flight during softmax and P V
+      ST::load(rv, Vp, ld, kn, T - 1, tid);   // next V tile: in flight during softmax and P V
       ldv(0, fb[0]);  // first V fragments: their latency hides behind the softmax arithmetic
       __builtin_amdgcn_sched_barrier(0);
       const bool mask = k0 + BKV - 1 > qw0;
@@ -214,10 +217,8 @@ __global__ __launch_bounds__(256, 2) void k_flash_fwd(const bf16* __restrict__ q
 #pragma unroll
         for (int c = 0; c < HD / 32; ++c) oacc[c] = mfma(fb[tu & 1][c], pf, oacc[c]);
       }
-    } else if (more) {
-      ST::load(rv, Vp, ld, k0 + BKV, T - 1, tid);
     }
-    if (more) {
+    {
       char* nk = smem + ((kt + 1) & 1) * (kKTile + kVTile);
       ST::store(rk, nk, KS, tid);
       ST::store(rv, nk + kKTile, VS, tid);
@@ -321,11 +322,12 @@ __global__ __launch_bounds__(256, 2) void k_flash_bwd_dq(const bf16* __restrict_
     ST::store(rk, kts, TS, tid);
     ST::store(rv, vs, KS, tid);
     __syncthreads();
-    if (kt + 1 < ntiles) {
-      ST::load(rk, Kp, ld, k0 + BKV, T - 1, tid);
-      ST::load(rv, Vp, ld, k0 + BKV, T - 1, tid);
+    {
+      const int kn = min(k0 + BKV, (ntiles - 1) * BKV);   // straight-line body, as in the forward kernel
+      ST::load(rk, Kp, ld, kn, T - 1, tid);
+      ST::load(rv, Vp, ld, kn, T - 1, tid);
     }
-    if (k0 <= qw0 + 31) {
+    {
       const bool mask = k0 + BKV - 1 > qw0;
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
@@ -465,11 +467,10 @@ __global__ __launch_bounds__(256) void k_flash_bwd_dkv(const bf16* __restrict__ 
   }
   __syncthreads();
   for (int step = 0; step < steps; ++step) {
-    const bool more = step + 1 < steps;
-    if (more) load_step(step + 1);
+    load_step(min(step + 1, steps - 1));   // straight-line body: after the last step this re-reads it
     const int qs = (qt0 + step % per_head) * BQ;
     const char* base = smem + (step & 1) * kBuf;
-    if (qs + BQ - 1 >= kw0) {  // some query of the tile sees a key of this wavefront
+    {  // a wavefront none of whose keys is visible to the tile's queries computes zeros
       const char* qsm = base;
       const char* dosm = base + kQTile;
       const char* qts = base + 2 * kQTile;
@@ -534,7 +535,7 @@ __global__ __launch_bounds__(256) void k_flash_bwd_dkv(const bf16* __restrict__ 
         }
       }
     }
-    if (more) store_step((step + 1) & 1);
+    store_step((step + 1) & 1);
     __syncthreads();
   }
   if (key < T) {
