@@ -23,7 +23,7 @@ namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;   // one staged 16-byte chunk (a native vector: stays in registers)
+// u32x4 (devutil.h): one staged 16-byte chunk; a native vector, so staged tiles stay in registers
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -81,6 +81,16 @@ struct Stage {
         reg[n] = *reinterpret_cast<const u32x4*>(X + (int64_t)r * ld + (c % kChunksPerRow) * 8);
       }
     }
+  }
+  // the same block through a buffer descriptor: voff0(tid) + row0 * row_bytes; rows past the end read as zero
+  __device__ __forceinline__ static uint32_t voff0(int tid, int n, uint32_t row_bytes) {
+    const int c = tid + 256 * n;
+    return (uint32_t)(c / kChunksPerRow) * row_bytes + (uint32_t)(c % kChunksPerRow) * 16u;
+  }
+  __device__ __forceinline__ static void bload(u32x4 (&reg)[NCH], rsrc_t rsrc, uint32_t row_bytes, uint32_t off, int tid) {
+#pragma unroll
+    for (int n = 0; n < NCH; ++n)
+      if (kChunks % 256 == 0 || tid + 256 * n < kChunks) reg[n] = buffer_load16(rsrc, voff0(tid, n, row_bytes) + off);
   }
   __device__ __forceinline__ static void store(const u32x4 (&reg)[NCH], char* tile, int stride, int tid) {
 #pragma unroll
@@ -397,152 +407,231 @@ __global__ __launch_bounds__(256, 2) void k_flash_bwd_dq(const bf16* __restrict_
 // ================================================================================ backward: dK, dV
 // Workgroup: 128 keys of one (sequence, kv head), 4 wavefronts x 32 keys, which it owns: their K
 // and V fragments stay in registers.  It walks the query heads of its group and, for each, the
-// query tiles (32 rows) from its first key onward.  Per tile: S[query][key] = Q K^T,
-// P = exp(S - lse[query]), dP = dO V^T, dS = P (dP - delta[query]),
-// dV^T[col][key] += dO^T P,  dK^T[col][key] += Q^T dS.
+// query tiles (32 rows) from its first key onward.  Per tile:
+//   phase 1  S' = Q K^T - lse/scale + mask bias,  dP' = dO V^T - delta           (2 * hd/16 MFMAs)
+//   phase 2  P = exp(scale S'),  dS = P dP'                                      (arithmetic only)
+//   phase 3  dV^T[col][key] += dO^T P,  dK^T[col][key] += Q^T dS                 (2 * hd/16 MFMAs)
+// The log-sum-exp, the causal mask and delta enter as the initial accumulators of phase 1, so phase 2
+// is a product, an exponential, a product and the conversions per element.
+// One wavefront per SIMD (the accumulators leave no room for two), so matrix work, arithmetic and
+// LDS latency overlap inside the wavefront, by software pipelining over the tiles:
+//   first half of an iteration   phase 1 of tile i+1 (operands already in registers), phase 2 of
+//                                tile i, LDS reads of tile i's phase 3 operands
+//   second half                  phase 3 of tile i, LDS reads of tile i+2's phase 1 operands and
+//                                initial accumulators
+// with one workgroup barrier between the halves.  Tiles rotate through three LDS buffers: tile i+2 is
+// written at the top of iteration i (its buffer was last read before the previous barrier), and the
+// global loads of tile i+3 are then in flight for a whole iteration.  Tiles past the end of the walk
+// carry lse = +inf, so they multiply through as zeros.
 template <int HD>
 __global__ __launch_bounds__(256) void k_flash_bwd_dkv(const bf16* __restrict__ qkv, const bf16* __restrict__ dO,
                                                        const float* __restrict__ lse, const float* __restrict__ delta,
                                                        bf16* __restrict__ dqkv, int T, int H, int Hkv, float scale) {
-  constexpr int BK = 128, BQ = 32;
-  constexpr int QS = HD * 2 + 16;   // Q and dO tiles [query][hd]
-  constexpr int TS = HD * 2 + 64;   // second copies of Q and dO, [query][hd], strided for the transpose read
-  constexpr int kQTile = BQ * QS, kTTile = BQ * TS;
-  constexpr int kBuf = 2 * kQTile + 2 * kTTile + 2 * BQ * 4;
-  __shared__ __attribute__((aligned(16))) char smem[2 * kBuf];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lk = lane & 31, hh = lane >> 5;
+  constexpr int BK = 128, BQ = 32, NK = HD / 16, NC = HD / 32;
+  constexpr int QS = HD * 2 + 16;   // Q and dO tiles [query][hd], read along hd
+  constexpr int TS = HD * 2 + 64;   // second copies, strided for the transpose read
+  constexpr int kDO = BQ * QS, kQT = 2 * BQ * QS, kDOT = kQT + BQ * TS;
+  constexpr int kNL = kDOT + BQ * TS;   // -lse / scale per query: 256 slots, the first 32 are read
+  constexpr int kND = kNL + 256 * 4;    // -delta per query, likewise
+  constexpr int kBuf = kND + 256 * 4;
+  __shared__ __attribute__((aligned(16))) char smem[3 * kBuf];
+  const int tid = threadIdx.x, lane = tid & 63, lk = lane & 31, hh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int kb = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
   const int rep = H / Hkv;
   const int64_t ld = (int64_t)(H + 2 * Hkv) * HD;
   const bf16* Kp = qkv + (int64_t)b * T * ld + (H + kvh) * HD;
   const bf16* Vp = qkv + (int64_t)b * T * ld + (H + Hkv + kvh) * HD;
   const int k0 = kb * BK, kw0 = k0 + wave * 32, key = kw0 + lk, keyc = min(key, T - 1);
-  const float scale_log2 = scale * kLog2e;
+  const float scale_log2 = scale * kLog2e, inv_scale = 1.f / scale;
 
-  bf16x8 kf[HD / 16], vf[HD / 16];
+  bf16x8 kf[NK], vf[NK];
   {
     const bf16* kr = Kp + (int64_t)keyc * ld + hh * 8;
     const bf16* vr = Vp + (int64_t)keyc * ld + hh * 8;
 #pragma unroll
-    for (int kk = 0; kk < HD / 16; ++kk) {
+    for (int kk = 0; kk < NK; ++kk) {
       kf[kk] = *reinterpret_cast<const bf16x8*>(kr + kk * 16);
       vf[kk] = *reinterpret_cast<const bf16x8*>(vr + kk * 16);
     }
   }
-  f32x16 dk[HD / 32], dv[HD / 32];
+  f32x16 dk[NC], dv[NC];
 #pragma unroll
-  for (int c = 0; c < HD / 32; ++c) { dk[c] = zero16(); dv[c] = zero16(); }
+  for (int c = 0; c < NC; ++c) { dk[c] = zero16(); dv[c] = zero16(); }
+  // Mask bias.  Accumulator register r = 4g+e of a tile that starts at query qs is query qs + 8g + 4hh + e.
+  // On the tile that starts at this wavefront's first key it sees this lane's key iff lk - 4hh <= 8g + e;
+  // later tiles see every key, earlier ones none.  bias = diag[r] * sel with diag = -1e30 (hidden on the
+  // diagonal tile) or -1e-30, and sel = 0 (later tile), 1 (diagonal: -1e-30 vanishes beside any score) or
+  // 1e38 (earlier tile: every entry ends below -1e8, and exp gives 0).
+  f32x16 diag;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) diag[r] = (lk - 4 * hh > 8 * (r / 4) + r % 4) ? -1e30f : -1e-30f;
 
-  const int qt0 = k0 / BQ, nqt = (T + BQ - 1) / BQ;   // query tiles that can see a key of this block
-  const int per_head = nqt - qt0;
-  const int steps = per_head * rep;
+  // the walk: query heads a of this kv head, for each the query tiles qt0 .. nqt-1
+  const int qt0 = k0 / BQ, nqt = (T + BQ - 1) / BQ;
+  const int steps = (nqt - qt0) * rep;
+  struct Walk { int a, qt, left; };
+  auto advance = [&](Walk& w) {
+    const bool wrap = w.qt == nqt - 1;
+    w.qt = wrap ? qt0 : w.qt + 1;
+    w.a = min(wrap ? w.a + 1 : w.a, H - 1);   // past the end: any valid head, the tile counts for nothing
+    w.left -= 1;
+  };
   typedef Stage<HD, BQ> SQ;
   u32x4 rq[SQ::NCH], rdo[SQ::NCH];
-  float st_lse = 0.f, st_dlt = 0.f;
-  auto load_step = [&](int step) {
-    const int a = kvh * rep + step / per_head;
-    const int qs = (qt0 + step % per_head) * BQ;
-    SQ::load(rq, qkv + (int64_t)b * T * ld + a * HD, ld, qs, T - 1, tid);
-    SQ::load(rdo, dO + (int64_t)b * T * H * HD + a * HD, (int64_t)H * HD, qs, T - 1, tid);
-    if (tid < BQ) {
-      const int qi = min(qs + tid, T - 1);
-      st_lse = lse[((int64_t)b * H + a) * T + qi] * kLog2e;
-      st_dlt = delta[((int64_t)b * H + a) * T + qi];
-    }
+  float st_l = 0.f, st_d = 0.f;
+  bool st_live = false;
+  // Q and dO of this sequence behind buffer descriptors: rows past T read as zero
+  const uint32_t q_row = (uint32_t)ld * 2u, do_row = (uint32_t)H * HD * 2u;
+  const rsrc_t q_rs = make_rsrc(qkv + (int64_t)b * T * ld, (uint32_t)(((int64_t)(T - 1) * ld + (int64_t)H * HD) * 2));
+  const rsrc_t do_rs = make_rsrc(dO + (int64_t)b * T * H * HD, (uint32_t)((int64_t)T * H * HD * 2));
+  // loads only: nothing here may touch a loaded value, or the wavefront would wait for memory on the spot
+  auto load_tile = [&](const Walk& w) {
+    const int qs = w.qt * BQ;
+    SQ::bload(rq, q_rs, q_row, (uint32_t)qs * q_row + (uint32_t)w.a * HD * 2u, tid);
+    SQ::bload(rdo, do_rs, do_row, (uint32_t)qs * do_row + (uint32_t)w.a * HD * 2u, tid);
+    const int qi = qs + (tid & (BQ - 1));
+    const int64_t at = ((int64_t)b * H + w.a) * T + min(qi, T - 1);
+    st_l = lse[at];
+    st_d = delta[at];
+    st_live = qi < T && w.left > 0;
   };
-  auto store_step = [&](int buf) {
-    char* base = smem + buf * kBuf;
+  auto store_tile = [&](int boff) {
+    char* base = smem + boff;
     SQ::store(rq, base, QS, tid);
-    SQ::store(rdo, base + kQTile, QS, tid);
-    SQ::store(rq, base + 2 * kQTile, TS, tid);
-    SQ::store(rdo, base + 2 * kQTile + kTTile, TS, tid);
-    if (tid < BQ) {
-      reinterpret_cast<float*>(base + 2 * kQTile + 2 * kTTile)[tid] = st_lse;
-      reinterpret_cast<float*>(base + 2 * kQTile + 2 * kTTile + BQ * 4)[tid] = st_dlt;
+    SQ::store(rdo, base + kDO, QS, tid);
+    SQ::store(rq, base + kQT, TS, tid);
+    SQ::store(rdo, base + kDOT, TS, tid);
+    // a row past the end of the sequence, or a tile past the end of the walk, gets lse = +inf:
+    // its probabilities are exactly zero
+    const float nl = -st_l * inv_scale;
+    reinterpret_cast<float*>(base + kNL)[tid] = st_live ? nl : -INFINITY;
+    reinterpret_cast<float*>(base + kND)[tid] = -st_d;
+  };
+  // phase 1 operands of the tile in buffer boff, which starts at query qs: f[2kk] = Q, f[2kk+1] = dO
+  // (A operand: row = query lk), and the initial accumulators
+  auto read_phase1 = [&](int boff, int qs, bf16x8 (&f)[2 * NK], f32x16& s, f32x16& dp) {
+    const char* base = smem + boff + lk * QS + hh * 16;
+#pragma unroll
+    for (int kk = 0; kk < NK; ++kk) {
+      f[2 * kk] = *reinterpret_cast<const bf16x8*>(base + kk * 32);
+      f[2 * kk + 1] = *reinterpret_cast<const bf16x8*>(base + kDO + kk * 32);
+    }
+    const float sel = qs == kw0 ? 1.f : (qs < kw0 ? 1e38f : 0.f);
+    const float* pl = reinterpret_cast<const float*>(smem + boff + kNL) + hh * 4;
+    const float* pd = reinterpret_cast<const float*>(smem + boff + kND) + hh * 4;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const float4 l = *reinterpret_cast<const float4*>(pl + g * 8);
+      const float4 d = *reinterpret_cast<const float4*>(pd + g * 8);
+      s[4 * g] = __builtin_fmaf(diag[4 * g], sel, l.x);
+      s[4 * g + 1] = __builtin_fmaf(diag[4 * g + 1], sel, l.y);
+      s[4 * g + 2] = __builtin_fmaf(diag[4 * g + 2], sel, l.z);
+      s[4 * g + 3] = __builtin_fmaf(diag[4 * g + 3], sel, l.w);
+      dp[4 * g] = d.x; dp[4 * g + 1] = d.y; dp[4 * g + 2] = d.z; dp[4 * g + 3] = d.w;
     }
   };
-  if (steps > 0) {
-    load_step(0);
-    store_step(0);
-  }
-  __syncthreads();
-  for (int step = 0; step < steps; ++step) {
-    load_step(min(step + 1, steps - 1));   // straight-line body: after the last step this re-reads it
-    const int qs = (qt0 + step % per_head) * BQ;
-    const char* base = smem + (step & 1) * kBuf;
-    {  // a wavefront none of whose keys is visible to the tile's queries computes zeros
-      const char* qsm = base;
-      const char* dosm = base + kQTile;
-      const char* qts = base + 2 * kQTile;
-      const char* dots = qts + kTTile;
-      const float* s_lse = reinterpret_cast<const float*>(base + 2 * kQTile + 2 * kTTile);
-      const float* s_dlt = s_lse + BQ;
-      f32x16 s = zero16(), dp = zero16();
-      bf16x8 fb[2][4];
-      const char* qr = qsm + lk * QS + hh * 16;     // A operand: row = query lk of the tile
-      const char* dr = dosm + lk * QS + hh * 16;
-      auto ldq = [&](int g, bf16x8 (&f)[4]) {
-        f[0] = *reinterpret_cast<const bf16x8*>(qr + (2 * g) * 32);
-        f[1] = *reinterpret_cast<const bf16x8*>(dr + (2 * g) * 32);
-        f[2] = *reinterpret_cast<const bf16x8*>(qr + (2 * g + 1) * 32);
-        f[3] = *reinterpret_cast<const bf16x8*>(dr + (2 * g + 1) * 32);
-      };
-      // group w of the second phase: w = 2u + (0: dO^T for dV, 1: Q^T for dK)
-      auto ldt = [&](int w, bf16x8 (&f)[4]) {
+  auto phase1 = [&](const bf16x8 (&f)[2 * NK], f32x16& s, f32x16& dp) {
 #pragma unroll
-        for (int c = 0; c < HD / 32; ++c) f[c] = read_tr((w & 1) ? qts : dots, TS, c * 32, 16 * (w >> 1), lane);
-      };
-      ldq(0, fb[0]);
-#pragma unroll
-      for (int g = 0; g < HD / 32; ++g) {
-        if (g + 1 < HD / 32) ldq(g + 1, fb[(g + 1) & 1]);
-        __builtin_amdgcn_sched_barrier(0);
-        s = mfma(fb[g & 1][0], kf[2 * g], s);
-        dp = mfma(fb[g & 1][1], vf[2 * g], dp);
-        s = mfma(fb[g & 1][2], kf[2 * g + 1], s);
-        dp = mfma(fb[g & 1][3], vf[2 * g + 1], dp);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      ldt(0, fb[0]);
-      __builtin_amdgcn_sched_barrier(0);
-      const bool mask = qs < kw0 + 31;
-      f32x16 p;
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int qi = g * 8 + hh * 4;   // accumulator rows 4g..4g+3 are queries qi..qi+3 of the tile
-        const float4 l4 = *reinterpret_cast<const float4*>(s_lse + qi);
-        const float4 d4 = *reinterpret_cast<const float4*>(s_dlt + qi);
-        const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int r = 4 * g + e;
-          float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(s[r], scale_log2, -lv[e]));
-          if (mask && key > qs + qi + e) pv = 0.f;
-          if (qs + qi + e >= T) pv = 0.f;     // rows past the end of the sequence are re-reads of row T-1
-          p[r] = pv;
-          s[r] = pv * (dp[r] - dv4[e]);
-        }
-      }
-#pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        if (w + 1 < 4) ldt(w + 1, fb[(w + 1) & 1]);
-        __builtin_amdgcn_sched_barrier(0);
-        const bf16x8 bf = pack8((w & 1) ? s : p, w >> 1);
-#pragma unroll
-        for (int c = 0; c < HD / 32; ++c) {
-          if (w & 1) dk[c] = mfma(fb[w & 1][c], bf, dk[c]);
-          else dv[c] = mfma(fb[w & 1][c], bf, dv[c]);
-        }
-      }
+    for (int kk = 0; kk < NK; ++kk) {
+      s = mfma(f[2 * kk], kf[kk], s);
+      dp = mfma(f[2 * kk + 1], vf[kk], dp);
     }
-    store_step((step + 1) & 1);
+  };
+
+  Walk w_ld = {kvh * rep, qt0, steps}, w_nx = w_ld;   // next tile to load; next tile whose phase 1 operands are read
+  int b0 = 0, b1 = kBuf, b2 = 2 * kBuf;
+  load_tile(w_ld); advance(w_ld);
+  store_tile(b0);
+  load_tile(w_ld); advance(w_ld);
+  store_tile(b1);
+  load_tile(w_ld); advance(w_ld);
+  __syncthreads();
+  bf16x8 f1[2 * NK];
+  f32x16 s_a, dp_a, s_b, dp_b;
+  read_phase1(b0, w_nx.qt * BQ, f1, s_a, dp_a); advance(w_nx);
+  phase1(f1, s_a, dp_a);
+  read_phase1(b1, w_nx.qt * BQ, f1, s_b, dp_b); advance(w_nx);
+
+  // one iteration: tile i's phase 1 result in (s_c, dp_c); tile i+1's initial accumulators in (s_n, dp_n)
+  // and its operands in f1.  On return (s_n, dp_n) hold tile i+1's result, (s_c, dp_c) tile i+2's start.
+  auto iteration = [&](f32x16& s_c, f32x16& dp_c, f32x16& s_n, f32x16& dp_n) {
+    // ---- top: tile i+2 into its buffer, tile i+3 on its way
+    store_tile(b2);
+    load_tile(w_ld); advance(w_ld);
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- first half, in NK slots fenced from each other: two MFMAs of tile i+1's phase 1, 16/NK
+    // elements of tile i's phase 2, two of the 2 NK operand fragments of tile i's phase 3
+    constexpr int EPS = 16 / NK;   // elements per slot: 2 (hd 128) or 4 (hd 64)
+    bf16x8 pf[2], dsf[2];
+    bf16x8 f3[2 * NK];             // in the order phase 3 uses them
+#pragma unroll
+    for (int kk = 0; kk < NK; ++kk) {
+      s_n = mfma(f1[2 * kk], kf[kk], s_n);
+      dp_n = mfma(f1[2 * kk + 1], vf[kk], dp_n);
+#pragma unroll
+      for (int j = 0; j < EPS; ++j) {
+        const int r = EPS * kk + j;
+        const float pv = __builtin_amdgcn_exp2f(s_c[r] * scale_log2);
+        pf[r / 8][r % 8] = (bf16)pv;
+        dsf[r / 8][r % 8] = (bf16)(pv * dp_c[r]);
+      }
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        // fragment m = (u * 2 + which) * NC + c: which 0 = dO^T (for dV), 1 = Q^T (for dK)
+        const int m = 2 * kk + j, c = m % NC, which = (m / NC) & 1, u = m / (2 * NC);
+        f3[m] = read_tr(smem + b0 + (which ? kQT : kDOT), TS, c * 32, 16 * u, lane);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
     __syncthreads();
+    // ---- second half, likewise: two MFMAs of phase 3, two operand fragments of tile i+2's phase 1, and
+    // in the first four slots a quarter of its initial accumulators
+    {
+      const int qs = w_nx.qt * BQ;
+      const float sel = qs == kw0 ? 1.f : (qs < kw0 ? 1e38f : 0.f);
+      const char* base = smem + b2 + lk * QS + hh * 16;
+      const float* pl = reinterpret_cast<const float*>(smem + b2 + kNL) + hh * 4;
+      const float* pd = reinterpret_cast<const float*>(smem + b2 + kND) + hh * 4;
+      float4 l4[4], d4[4];
+      auto init_group = [&](int g) {
+        s_c[4 * g] = __builtin_fmaf(diag[4 * g], sel, l4[g].x);
+        s_c[4 * g + 1] = __builtin_fmaf(diag[4 * g + 1], sel, l4[g].y);
+        s_c[4 * g + 2] = __builtin_fmaf(diag[4 * g + 2], sel, l4[g].z);
+        s_c[4 * g + 3] = __builtin_fmaf(diag[4 * g + 3], sel, l4[g].w);
+        dp_c[4 * g] = d4[g].x; dp_c[4 * g + 1] = d4[g].y; dp_c[4 * g + 2] = d4[g].z; dp_c[4 * g + 3] = d4[g].w;
+      };
+#pragma unroll
+      for (int kk = 0; kk < NK; ++kk) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          const int m = 2 * kk + j, c = m % NC, which = (m / NC) & 1, u = m / (2 * NC);
+          if (which) dk[c] = mfma(f3[m], dsf[u], dk[c]);
+          else dv[c] = mfma(f3[m], pf[u], dv[c]);
+        }
+        f1[2 * kk] = *reinterpret_cast<const bf16x8*>(base + kk * 32);
+        f1[2 * kk + 1] = *reinterpret_cast<const bf16x8*>(base + kDO + kk * 32);
+        if (kk < 4) {
+          l4[kk] = *reinterpret_cast<const float4*>(pl + kk * 8);
+          d4[kk] = *reinterpret_cast<const float4*>(pd + kk * 8);
+        }
+        if (kk >= 1 && kk <= 4) init_group(kk - 1);   // a slot after its reads: their latency is covered
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (NK <= 4) init_group(3);
+      advance(w_nx);
+    }
+    const int t = b0; b0 = b1; b1 = b2; b2 = t;
+  };
+  for (int step = 0; step < steps; step += 2) {
+    iteration(s_a, dp_a, s_b, dp_b);
+    iteration(s_b, dp_b, s_a, dp_a);
   }
   if (key < T) {
     bf16* krow = dqkv + ((int64_t)b * T + key) * ld + (H + kvh) * HD;
     bf16* vrow = dqkv + ((int64_t)b * T + key) * ld + (H + Hkv + kvh) * HD;
 #pragma unroll
-    for (int c = 0; c < HD / 32; ++c)
+    for (int c = 0; c < NC; ++c)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         uint2 w;

@@ -37,7 +37,6 @@ typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) int i32x4;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __amdgpu_buffer_rsrc_t rsrc_t;
 
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int kThreads = 512;
@@ -49,9 +48,6 @@ constexpr int kCRowBytes = 528;                 // output staging: 256 bf16 + 16
 static_assert(64 * kKRowBytes == kTileBytes, "both tile layouts have the same footprint");
 static_assert(256 * kCRowBytes <= kLdsBytes, "output staging fits in the operand buffers");
 
-__device__ __forceinline__ rsrc_t make_rsrc(const void* p, uint32_t bytes) {
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
-}
 // 16 bytes at byte offset voff; zero if voff is at or past the end of the buffer
 __device__ __forceinline__ uint4 bload(rsrc_t rsrc, uint32_t voff) {
   i32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)voff, 0, 0);
