@@ -408,33 +408,75 @@ __global__ __launch_bounds__(256, 2) void k_flash_bwd_dq(const bf16* __restrict_
 // Workgroup: 128 keys of one (sequence, kv head), 4 wavefronts x 32 keys, which it owns: their K
 // and V fragments stay in registers.  It walks the query heads of its group and, for each, the
 // query tiles (32 rows) from its first key onward.  Per tile:
-//   phase 1  S' = Q K^T - lse/scale + mask bias,  dP' = dO V^T - delta           (2 * hd/16 MFMAs)
-//   phase 2  P = exp(scale S'),  dS = P dP'                                      (arithmetic only)
-//   phase 3  dV^T[col][key] += dO^T P,  dK^T[col][key] += Q^T dS                 (2 * hd/16 MFMAs)
-// The log-sum-exp, the causal mask and delta enter as the initial accumulators of phase 1, so phase 2
-// is a product, an exponential, a product and the conversions per element.
+//   phase 1  S' = Q K^T - lse/scale + mask bias,  dP' = delta - dO V^T           (2 * hd/16 MFMAs)
+//   phase 2  P = exp(scale S'),  dS' = P dP' = -dS                               (arithmetic only)
+//   phase 3  dV^T[col][key] += dO^T P,  -dK^T[col][key] += Q^T dS'               (2 * hd/16 MFMAs)
+// The log-sum-exp, the causal mask and delta enter as the initial accumulators of phase 1 (V is
+// held negated so that delta enters unchanged), so phase 2 is a product, an exponential, a product and
+// the conversions per element.
+//
 // One wavefront per SIMD (the accumulators leave no room for two), so matrix work, arithmetic and
 // LDS latency overlap inside the wavefront, by software pipelining over the tiles:
 //   first half of an iteration   phase 1 of tile i+1 (operands already in registers), phase 2 of
 //                                tile i, LDS reads of tile i's phase 3 operands
 //   second half                  phase 3 of tile i, LDS reads of tile i+2's phase 1 operands and
 //                                initial accumulators
-// with one workgroup barrier between the halves.  Tiles rotate through three LDS buffers: tile i+2 is
-// written at the top of iteration i (its buffer was last read before the previous barrier), and the
-// global loads of tile i+3 are then in flight for a whole iteration.  Tiles past the end of the walk
-// carry lse = +inf, so they multiply through as zeros.
+// with one workgroup barrier between the halves.  Each half is cut into slots of two MFMAs plus their
+// share of the other work, fenced from each other, because a wavefront overlaps arithmetic only with
+// the MFMA issued just before it.
+//
+// Q, dO, lse and delta tiles go from memory straight into LDS (buffer loads with the LDS modifier: no
+// staging registers, no LDS store instructions), kDepth tiles ahead, in a ring of kDepth + 1 buffers.
+// A load instruction fills 1 KiB of LDS in lane order, so the layout is row-major without padding and
+// the 16-byte chunks of a row are permuted by an XOR with bits of the row number, applied on the memory
+// side of the copy; the permutation makes both the row-wise reads of phase 1 and the transpose reads
+// of phase 3 bank-conflict free.  These loads are issued from assembly, outside the compiler's wait insertion: the
+// wavefront waits for its own (vmcnt, counted by hand) before the barrier after which a tile is first read.
+// Rows past the end of the sequence and tiles past the end of the walk read as zeros (offsets beyond
+// the buffer descriptors), and zero rows of Q and dO contribute nothing to either gradient.
+// Buffer loads with the LDS modifier, written as assembly so that the compiler's wait insertion does not
+// see them: it would otherwise make the first LDS read after every such load wait for it (it cannot tell
+// that the read is from another ring buffer), which would undo the prefetch.  One instruction copies
+// 64 x 16 bytes (or 64 x 4) from the lanes' buffer offsets to LDS at lds .. lds + 1024 (256) in lane
+// order; offsets at or past the descriptor's size deliver zeros.  Tracked by vmcnt like any load.
+typedef __attribute__((address_space(3))) void* lds_ptr;
+__device__ __forceinline__ u32x4 make_desc(const void* p, uint32_t bytes) {
+  const uint64_t a = (uint64_t)p;
+  u32x4 d = {(uint32_t)a, (uint32_t)(a >> 32) & 0xffffu, bytes, 0x00020000u};
+  return d;
+}
+__device__ __forceinline__ void load_to_lds16(u32x4 desc, lds_ptr lds, uint32_t voff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds), "v"(voff), "s"(desc) : "memory", "m0");
+}
+__device__ __forceinline__ void load_to_lds4(u32x4 desc, lds_ptr lds, uint32_t voff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds" ::"s"(lds), "v"(voff), "s"(desc) : "memory", "m0");
+}
+
+template <int HD>
+struct DkvGeom {
+  static constexpr int BQ = 32, NK = HD / 16, NC = HD / 32;
+  static constexpr int RB = HD * 2;            // bytes per tile row
+  static constexpr int CPR = HD / 8;           // 16-byte chunks per row
+  static constexpr int kTile = BQ * RB;
+  static constexpr int NJ = kTile / 4096;      // tile loads per thread and matrix (256 threads x 16 bytes each)
+  static constexpr int kDO = kTile, kL = 2 * kTile, kD = kL + 1024, kBuf = kD + 1024;
+  static constexpr int kDepth = 4, kRing = kDepth + 1;
+  static constexpr int NI = 2 * NJ + 2;        // load instructions per thread and tile
+  // chunk permutation key of a row: distinct over 16 consecutive rows (aligned), and over rows 4m..4m+3
+  // distinct in the bits above the two lowest
+  __device__ __forceinline__ static int key(int row) {
+    return HD == 128 ? ((row & 3) << 2) | ((row >> 2) & 3) : (((row >> 1) & 1) << 2) | ((row >> 2) & 3);
+  }
+};
+
 template <int HD>
 __global__ __launch_bounds__(256) void k_flash_bwd_dkv(const bf16* __restrict__ qkv, const bf16* __restrict__ dO,
                                                        const float* __restrict__ lse, const float* __restrict__ delta,
                                                        bf16* __restrict__ dqkv, int T, int H, int Hkv, float scale) {
-  constexpr int BK = 128, BQ = 32, NK = HD / 16, NC = HD / 32;
-  constexpr int QS = HD * 2 + 16;   // Q and dO tiles [query][hd], read along hd
-  constexpr int TS = HD * 2 + 64;   // second copies, strided for the transpose read
-  constexpr int kDO = BQ * QS, kQT = 2 * BQ * QS, kDOT = kQT + BQ * TS;
-  constexpr int kNL = kDOT + BQ * TS;   // -lse / scale per query: 256 slots, the first 32 are read
-  constexpr int kND = kNL + 256 * 4;    // -delta per query, likewise
-  constexpr int kBuf = kND + 256 * 4;
-  __shared__ __attribute__((aligned(16))) char smem[3 * kBuf];
+  typedef DkvGeom<HD> G;
+  constexpr int BK = 128, BQ = G::BQ, NK = G::NK, NC = G::NC, RB = G::RB, CPR = G::CPR, NJ = G::NJ;
+  constexpr int kTile = G::kTile, kDO = G::kDO, kL = G::kL, kD = G::kD, kBuf = G::kBuf, kRing = G::kRing, kDepth = G::kDepth;
+  __shared__ __attribute__((aligned(1024))) char smem[kRing * kBuf];
   const int tid = threadIdx.x, lane = tid & 63, lk = lane & 31, hh = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int kb = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
@@ -443,19 +485,21 @@ __global__ __launch_bounds__(256) void k_flash_bwd_dkv(const bf16* __restrict__ 
   const bf16* Kp = qkv + (int64_t)b * T * ld + (H + kvh) * HD;
   const bf16* Vp = qkv + (int64_t)b * T * ld + (H + Hkv + kvh) * HD;
   const int k0 = kb * BK, kw0 = k0 + wave * 32, key = kw0 + lk, keyc = min(key, T - 1);
-  const float scale_log2 = scale * kLog2e, inv_scale = 1.f / scale;
+  const float scale_log2 = scale * kLog2e, neg_inv_scale = -1.f / scale;
 
-  bf16x8 kf[NK], vf[NK];
+  bf16x8 kf[NK], vf[NK];   // vf = -V
   {
     const bf16* kr = Kp + (int64_t)keyc * ld + hh * 8;
     const bf16* vr = Vp + (int64_t)keyc * ld + hh * 8;
 #pragma unroll
     for (int kk = 0; kk < NK; ++kk) {
       kf[kk] = *reinterpret_cast<const bf16x8*>(kr + kk * 16);
-      vf[kk] = *reinterpret_cast<const bf16x8*>(vr + kk * 16);
+      u32x4 v = *reinterpret_cast<const u32x4*>(vr + kk * 16);
+      v ^= 0x80008000u;
+      vf[kk] = __builtin_bit_cast(bf16x8, v);
     }
   }
-  f32x16 dk[NC], dv[NC];
+  f32x16 dk[NC], dv[NC];   // dk accumulates -dK / scale
 #pragma unroll
   for (int c = 0; c < NC; ++c) { dk[c] = zero16(); dv[c] = zero16(); }
   // Mask bias.  Accumulator register r = 4g+e of a tile that starts at query qs is query qs + 8g + 4hh + e.
@@ -467,6 +511,36 @@ __global__ __launch_bounds__(256) void k_flash_bwd_dkv(const bf16* __restrict__ 
 #pragma unroll
   for (int r = 0; r < 16; ++r) diag[r] = (lk - 4 * hh > 8 * (r / 4) + r % 4) ? -1e30f : -1e-30f;
 
+  // ---- lane constants of the LDS reads (byte offsets inside a ring buffer)
+  // phase 1: row lk, chunk (2 kk + hh) permuted; kk enters by XOR with kk * 32
+  const int p1_base = lk * RB + ((hh ^ G::key(lk)) << 4);
+  // phase 3 (transpose reads, see read_tr): 16-lane group position i = row, w = chunk, half = 8-byte half;
+  // rows 16u + 8hi + 4hh + i, chunks 4c + w.  u enters as a constant offset, c by XOR with c * 64.
+  int p3_base[2];
+  {
+    const int sl = lane & 15, i = sl >> 2, w = ((lane >> 4) & 1) * 2 + ((sl & 3) >> 1), half = sl & 1;
+#pragma unroll
+    for (int hi = 0; hi < 2; ++hi) {
+      const int row = 8 * hi + 4 * hh + i;
+      p3_base[hi] = row * RB + (((G::key(row) & 12) | (w ^ (G::key(row) & 3))) << 4) + half * 8;
+    }
+  }
+  // ---- lane constants of the tile loads: instruction j of this wavefront fills chunks (4j + wave) * 64 + lane
+  // of the tile; a chunk at row, position p holds the row's chunk p ^ key(row)
+  const uint32_t q_row = (uint32_t)ld * 2u, do_row = (uint32_t)H * HD * 2u;
+  uint32_t ldq[NJ], ldo[NJ];
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int q = (4 * j + wave) * 64 + lane, row = q / CPR, pos = q % CPR;
+    ldq[j] = (uint32_t)row * q_row + (uint32_t)((pos ^ G::key(row)) << 4);
+    ldo[j] = (uint32_t)row * do_row + (uint32_t)((pos ^ G::key(row)) << 4);
+  }
+  const uint32_t ldl = (uint32_t)(lane & (BQ - 1)) * 4u;
+  const u32x4 q_rs = make_desc(qkv + (int64_t)b * T * ld, (uint32_t)(((int64_t)(T - 1) * ld + (int64_t)H * HD) * 2));
+  const u32x4 do_rs = make_desc(dO + (int64_t)b * T * H * HD, (uint32_t)((int64_t)T * H * HD * 2));
+  const u32x4 l_rs = make_desc(lse + (int64_t)b * H * T, (uint32_t)((int64_t)H * T * 4));
+  const u32x4 d_rs = make_desc(delta + (int64_t)b * H * T, (uint32_t)((int64_t)H * T * 4));
+
   // the walk: query heads a of this kv head, for each the query tiles qt0 .. nqt-1
   const int qt0 = k0 / BQ, nqt = (T + BQ - 1) / BQ;
   const int steps = (nqt - qt0) * rep;
@@ -474,62 +548,66 @@ __global__ __launch_bounds__(256) void k_flash_bwd_dkv(const bf16* __restrict__ 
   auto advance = [&](Walk& w) {
     const bool wrap = w.qt == nqt - 1;
     w.qt = wrap ? qt0 : w.qt + 1;
-    w.a = min(wrap ? w.a + 1 : w.a, H - 1);   // past the end: any valid head, the tile counts for nothing
+    w.a = wrap ? w.a + 1 : w.a;
     w.left -= 1;
   };
-  typedef Stage<HD, BQ> SQ;
-  u32x4 rq[SQ::NCH], rdo[SQ::NCH];
-  float st_l = 0.f, st_d = 0.f;
-  bool st_live = false;
-  // Q and dO of this sequence behind buffer descriptors: rows past T read as zero
-  const uint32_t q_row = (uint32_t)ld * 2u, do_row = (uint32_t)H * HD * 2u;
-  const rsrc_t q_rs = make_rsrc(qkv + (int64_t)b * T * ld, (uint32_t)(((int64_t)(T - 1) * ld + (int64_t)H * HD) * 2));
-  const rsrc_t do_rs = make_rsrc(dO + (int64_t)b * T * H * HD, (uint32_t)((int64_t)T * H * HD * 2));
-  // loads only: nothing here may touch a loaded value, or the wavefront would wait for memory on the spot
-  auto load_tile = [&](const Walk& w) {
+  auto ring_next = [&](int boff) { return boff + kBuf == kRing * kBuf ? 0 : boff + kBuf; };
+  // loads of tile w into the ring buffer at boff; a tile past the end of the walk is fetched from beyond
+  // every buffer, i.e. as zeros
+  auto load_tile = [&](const Walk& w, int boff) {
+    const uint32_t dead = w.left > 0 ? 0u : 0x80000000u;
+    const uint32_t qs = (uint32_t)w.qt * BQ;
+    const uint32_t oq = (qs * q_row + (uint32_t)w.a * HD * 2u) | dead, od = (qs * do_row + (uint32_t)w.a * HD * 2u) | dead;
+    const uint32_t ol = (((uint32_t)w.a * T + qs) * 4u) | dead;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      load_to_lds16(q_rs, (lds_ptr)(smem + boff + (4 * j + wave) * 1024), ldq[j] + oq);
+      load_to_lds16(do_rs, (lds_ptr)(smem + boff + kDO + (4 * j + wave) * 1024), ldo[j] + od);
+    }
+    load_to_lds4(l_rs, (lds_ptr)(smem + boff + kL + wave * 256), ldl + ol);
+    load_to_lds4(d_rs, (lds_ptr)(smem + boff + kD + wave * 256), ldl + ol);
+  };
+  // wait until all but the newest kDepth - 2 tiles of this wavefront's loads and all its LDS reads are
+  // done, then meet the other wavefronts
+  auto tiles_barrier = [&]() {
+    constexpr int n = (kDepth - 2) * G::NI;
+    static_assert(n < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt((n & 15) | ((n >> 4) << 14) | (7 << 4) | (0 << 8));   // vmcnt(n) lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
+  };
+  // phase 1 operands of the tile at boff, which starts at query qs: f[2kk] = Q, f[2kk+1] = dO (A operand:
+  // row = query lk), and the initial accumulators
+  auto read_tr2 = [&](int lo, int hi2) {
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    const s16x4 l = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(smem + lo));
+    const s16x4 h = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(smem + hi2));
+    const s16x8 v = {l[0], l[1], l[2], l[3], h[0], h[1], h[2], h[3]};
+    return __builtin_bit_cast(bf16x8, v);
+  };
+  auto read_f1 = [&](int boff, int kk, bf16x8 (&f)[2 * NK]) {
+    const char* p = smem + ((p1_base + boff) ^ (kk * 32));
+    f[2 * kk] = *reinterpret_cast<const bf16x8*>(p);
+    f[2 * kk + 1] = *reinterpret_cast<const bf16x8*>(p + kDO);
+  };
+  auto init_group = [&](int g, float sel, const float4& l, const float4& d, f32x16& s, f32x16& dp) {
+    s[4 * g] = __builtin_fmaf(diag[4 * g], sel, l.x * neg_inv_scale);
+    s[4 * g + 1] = __builtin_fmaf(diag[4 * g + 1], sel, l.y * neg_inv_scale);
+    s[4 * g + 2] = __builtin_fmaf(diag[4 * g + 2], sel, l.z * neg_inv_scale);
+    s[4 * g + 3] = __builtin_fmaf(diag[4 * g + 3], sel, l.w * neg_inv_scale);
+    dp[4 * g] = d.x; dp[4 * g + 1] = d.y; dp[4 * g + 2] = d.z; dp[4 * g + 3] = d.w;
+  };
+  auto tile_sel = [&](const Walk& w) {
     const int qs = w.qt * BQ;
-    SQ::bload(rq, q_rs, q_row, (uint32_t)qs * q_row + (uint32_t)w.a * HD * 2u, tid);
-    SQ::bload(rdo, do_rs, do_row, (uint32_t)qs * do_row + (uint32_t)w.a * HD * 2u, tid);
-    const int qi = qs + (tid & (BQ - 1));
-    const int64_t at = ((int64_t)b * H + w.a) * T + min(qi, T - 1);
-    st_l = lse[at];
-    st_d = delta[at];
-    st_live = qi < T && w.left > 0;
+    return qs == kw0 ? 1.f : (qs < kw0 ? 1e38f : 0.f);
   };
-  auto store_tile = [&](int boff) {
-    char* base = smem + boff;
-    SQ::store(rq, base, QS, tid);
-    SQ::store(rdo, base + kDO, QS, tid);
-    SQ::store(rq, base + kQT, TS, tid);
-    SQ::store(rdo, base + kDOT, TS, tid);
-    // a row past the end of the sequence, or a tile past the end of the walk, gets lse = +inf:
-    // its probabilities are exactly zero
-    const float nl = -st_l * inv_scale;
-    reinterpret_cast<float*>(base + kNL)[tid] = st_live ? nl : -INFINITY;
-    reinterpret_cast<float*>(base + kND)[tid] = -st_d;
-  };
-  // phase 1 operands of the tile in buffer boff, which starts at query qs: f[2kk] = Q, f[2kk+1] = dO
-  // (A operand: row = query lk), and the initial accumulators
-  auto read_phase1 = [&](int boff, int qs, bf16x8 (&f)[2 * NK], f32x16& s, f32x16& dp) {
-    const char* base = smem + boff + lk * QS + hh * 16;
+  auto read_phase1 = [&](int boff, float sel, bf16x8 (&f)[2 * NK], f32x16& s, f32x16& dp) {
 #pragma unroll
-    for (int kk = 0; kk < NK; ++kk) {
-      f[2 * kk] = *reinterpret_cast<const bf16x8*>(base + kk * 32);
-      f[2 * kk + 1] = *reinterpret_cast<const bf16x8*>(base + kDO + kk * 32);
-    }
-    const float sel = qs == kw0 ? 1.f : (qs < kw0 ? 1e38f : 0.f);
-    const float* pl = reinterpret_cast<const float*>(smem + boff + kNL) + hh * 4;
-    const float* pd = reinterpret_cast<const float*>(smem + boff + kND) + hh * 4;
+    for (int kk = 0; kk < NK; ++kk) read_f1(boff, kk, f);
+    const float* pl = reinterpret_cast<const float*>(smem + boff + kL) + hh * 4;
+    const float* pd = reinterpret_cast<const float*>(smem + boff + kD) + hh * 4;
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      const float4 l = *reinterpret_cast<const float4*>(pl + g * 8);
-      const float4 d = *reinterpret_cast<const float4*>(pd + g * 8);
-      s[4 * g] = __builtin_fmaf(diag[4 * g], sel, l.x);
-      s[4 * g + 1] = __builtin_fmaf(diag[4 * g + 1], sel, l.y);
-      s[4 * g + 2] = __builtin_fmaf(diag[4 * g + 2], sel, l.z);
-      s[4 * g + 3] = __builtin_fmaf(diag[4 * g + 3], sel, l.w);
-      dp[4 * g] = d.x; dp[4 * g + 1] = d.y; dp[4 * g + 2] = d.z; dp[4 * g + 3] = d.w;
-    }
+    for (int g = 0; g < 4; ++g)
+      init_group(g, sel, *reinterpret_cast<const float4*>(pl + g * 8), *reinterpret_cast<const float4*>(pd + g * 8), s, dp);
   };
   auto phase1 = [&](const bf16x8 (&f)[2 * NK], f32x16& s, f32x16& dp) {
 #pragma unroll
@@ -540,28 +618,29 @@ __global__ __launch_bounds__(256) void k_flash_bwd_dkv(const bf16* __restrict__ 
   };
 
   Walk w_ld = {kvh * rep, qt0, steps}, w_nx = w_ld;   // next tile to load; next tile whose phase 1 operands are read
-  int b0 = 0, b1 = kBuf, b2 = 2 * kBuf;
-  load_tile(w_ld); advance(w_ld);
-  store_tile(b0);
-  load_tile(w_ld); advance(w_ld);
-  store_tile(b1);
-  load_tile(w_ld); advance(w_ld);
-  __syncthreads();
+  int b_ld = 0, b_cur = 0, b_nx = 0;                  // their ring buffers, and the current tile's
+#pragma unroll
+  for (int t = 0; t < kDepth; ++t) { load_tile(w_ld, b_ld); advance(w_ld); b_ld = ring_next(b_ld); }
+  tiles_barrier();
   bf16x8 f1[2 * NK];
   f32x16 s_a, dp_a, s_b, dp_b;
-  read_phase1(b0, w_nx.qt * BQ, f1, s_a, dp_a); advance(w_nx);
+  read_phase1(b_nx, tile_sel(w_nx), f1, s_a, dp_a); advance(w_nx); b_nx = ring_next(b_nx);
   phase1(f1, s_a, dp_a);
-  read_phase1(b1, w_nx.qt * BQ, f1, s_b, dp_b); advance(w_nx);
+  read_phase1(b_nx, tile_sel(w_nx), f1, s_b, dp_b); advance(w_nx); b_nx = ring_next(b_nx);
 
   // one iteration: tile i's phase 1 result in (s_c, dp_c); tile i+1's initial accumulators in (s_n, dp_n)
   // and its operands in f1.  On return (s_n, dp_n) hold tile i+1's result, (s_c, dp_c) tile i+2's start.
   auto iteration = [&](f32x16& s_c, f32x16& dp_c, f32x16& s_n, f32x16& dp_n) {
-    // ---- top: tile i+2 into its buffer, tile i+3 on its way
-    store_tile(b2);
-    load_tile(w_ld); advance(w_ld);
+    // ---- top: tile i + kDepth on its way, into the buffer tile i-1 left at the last barrier
+    load_tile(w_ld, b_ld); advance(w_ld); b_ld = ring_next(b_ld);
+    int p3[2][NC];   // addresses of the transpose reads of tile i, by (hi, c)
+#pragma unroll
+    for (int hi = 0; hi < 2; ++hi)
+#pragma unroll
+      for (int c = 0; c < NC; ++c) p3[hi][c] = (p3_base[hi] + b_cur) ^ (c * 64);
     __builtin_amdgcn_sched_barrier(0);
-    // ---- first half, in NK slots fenced from each other: two MFMAs of tile i+1's phase 1, 16/NK
-    // elements of tile i's phase 2, two of the 2 NK operand fragments of tile i's phase 3
+    // ---- first half, in NK slots: two MFMAs of tile i+1's phase 1, 16/NK elements of tile i's phase 2,
+    // two of the 2 NK operand fragments of tile i's phase 3
     constexpr int EPS = 16 / NK;   // elements per slot: 2 (hd 128) or 4 (hd 64)
     bf16x8 pf[2], dsf[2];
     bf16x8 f3[2 * NK];             // in the order phase 3 uses them
@@ -580,27 +659,19 @@ __global__ __launch_bounds__(256) void k_flash_bwd_dkv(const bf16* __restrict__ 
       for (int j = 0; j < 2; ++j) {
         // fragment m = (u * 2 + which) * NC + c: which 0 = dO^T (for dV), 1 = Q^T (for dK)
         const int m = 2 * kk + j, c = m % NC, which = (m / NC) & 1, u = m / (2 * NC);
-        f3[m] = read_tr(smem + b0 + (which ? kQT : kDOT), TS, c * 32, 16 * u, lane);
+        const int off = (which ? 0 : kDO) + 16 * u * RB;
+        f3[m] = read_tr2(p3[0][c] + off, p3[1][c] + off);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
-    __syncthreads();
+    tiles_barrier();   // tile i+2 is complete
     // ---- second half, likewise: two MFMAs of phase 3, two operand fragments of tile i+2's phase 1, and
-    // in the first four slots a quarter of its initial accumulators
+    // its initial accumulators a slot after their reads
     {
-      const int qs = w_nx.qt * BQ;
-      const float sel = qs == kw0 ? 1.f : (qs < kw0 ? 1e38f : 0.f);
-      const char* base = smem + b2 + lk * QS + hh * 16;
-      const float* pl = reinterpret_cast<const float*>(smem + b2 + kNL) + hh * 4;
-      const float* pd = reinterpret_cast<const float*>(smem + b2 + kND) + hh * 4;
+      const float sel = tile_sel(w_nx);
+      const float* pl = reinterpret_cast<const float*>(smem + b_nx + kL) + hh * 4;
+      const float* pd = reinterpret_cast<const float*>(smem + b_nx + kD) + hh * 4;
       float4 l4[4], d4[4];
-      auto init_group = [&](int g) {
-        s_c[4 * g] = __builtin_fmaf(diag[4 * g], sel, l4[g].x);
-        s_c[4 * g + 1] = __builtin_fmaf(diag[4 * g + 1], sel, l4[g].y);
-        s_c[4 * g + 2] = __builtin_fmaf(diag[4 * g + 2], sel, l4[g].z);
-        s_c[4 * g + 3] = __builtin_fmaf(diag[4 * g + 3], sel, l4[g].w);
-        dp_c[4 * g] = d4[g].x; dp_c[4 * g + 1] = d4[g].y; dp_c[4 * g + 2] = d4[g].z; dp_c[4 * g + 3] = d4[g].w;
-      };
 #pragma unroll
       for (int kk = 0; kk < NK; ++kk) {
 #pragma unroll
@@ -609,34 +680,35 @@ __global__ __launch_bounds__(256) void k_flash_bwd_dkv(const bf16* __restrict__ 
           if (which) dk[c] = mfma(f3[m], dsf[u], dk[c]);
           else dv[c] = mfma(f3[m], pf[u], dv[c]);
         }
-        f1[2 * kk] = *reinterpret_cast<const bf16x8*>(base + kk * 32);
-        f1[2 * kk + 1] = *reinterpret_cast<const bf16x8*>(base + kDO + kk * 32);
+        read_f1(b_nx, kk, f1);
         if (kk < 4) {
           l4[kk] = *reinterpret_cast<const float4*>(pl + kk * 8);
           d4[kk] = *reinterpret_cast<const float4*>(pd + kk * 8);
         }
-        if (kk >= 1 && kk <= 4) init_group(kk - 1);   // a slot after its reads: their latency is covered
+        if (kk >= 1 && kk <= 4) init_group(kk - 1, sel, l4[kk - 1], d4[kk - 1], s_c, dp_c);
         __builtin_amdgcn_sched_barrier(0);
       }
-      if (NK <= 4) init_group(3);
-      advance(w_nx);
+      if (NK <= 4) init_group(3, sel, l4[3], d4[3], s_c, dp_c);
+      advance(w_nx); b_nx = ring_next(b_nx);
     }
-    const int t = b0; b0 = b1; b1 = b2; b2 = t;
+    b_cur = ring_next(b_cur);
   };
   for (int step = 0; step < steps; step += 2) {
     iteration(s_a, dp_a, s_b, dp_b);
     iteration(s_b, dp_b, s_a, dp_a);
   }
+  __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (15 << 8));   // vmcnt(0): no load may still be writing LDS at the end
   if (key < T) {
     bf16* krow = dqkv + ((int64_t)b * T + key) * ld + (H + kvh) * HD;
     bf16* vrow = dqkv + ((int64_t)b * T + key) * ld + (H + Hkv + kvh) * HD;
+    const float ks = -scale;
 #pragma unroll
     for (int c = 0; c < NC; ++c)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         uint2 w;
-        w.x = pack_bf16(dk[c][4 * g] * scale, dk[c][4 * g + 1] * scale);
-        w.y = pack_bf16(dk[c][4 * g + 2] * scale, dk[c][4 * g + 3] * scale);
+        w.x = pack_bf16(dk[c][4 * g] * ks, dk[c][4 * g + 1] * ks);
+        w.y = pack_bf16(dk[c][4 * g + 2] * ks, dk[c][4 * g + 3] * ks);
         *reinterpret_cast<uint2*>(krow + c * 32 + g * 8 + hh * 4) = w;
         w.x = pack_bf16(dv[c][4 * g], dv[c][4 * g + 1]);
         w.y = pack_bf16(dv[c][4 * g + 2], dv[c][4 * g + 3]);
@@ -648,7 +720,9 @@ __global__ __launch_bounds__(256) void k_flash_bwd_dkv(const bf16* __restrict__ 
 }  // namespace
 
 bool attention_flash_supported(int B, int T, int H, int Hkv, int hd) {
-  return (hd == 64 || hd == 128) && B >= 1 && T >= 1 && B <= 65535 && H <= 65535 && H % Hkv == 0;
+  // one sequence's rows of qkv, and its lse block, are addressed with 31-bit byte offsets
+  return (hd == 64 || hd == 128) && B >= 1 && T >= 1 && B <= 65535 && H <= 65535 && H % Hkv == 0 &&
+         (int64_t)T * (H + 2 * Hkv) * hd * 2 < (1ll << 31) && (int64_t)T * H * 4 < (1ll << 31);
 }
 
 void attention_flash_fwd(hipStream_t s, int B, int T, int H, int Hkv, int hd, const void* qkv, void* o, float* lse) {
