@@ -65,6 +65,14 @@ __device__ __forceinline__ bf16x8 read_tr(const char* tile, int RS, int col_base
   return __builtin_bit_cast(bf16x8, v);
 }
 
+// Workgroups are dealt to the 8 XCDs (each with its own L2) in turn: linear id L runs on XCD L % 8.
+// This renumbering of 0..N-1 gives every XCD one contiguous range, so that workgroups with neighbouring
+// numbers, which here share the K/V (or Q/dO) rows they stream, meet in one L2.
+__device__ __forceinline__ int xcd_major(int L, int N) {
+  const int per = N / 8, rem = N % 8, x = L % 8;
+  return x * per + min(x, rem) + L / 8;
+}
+
 // ---- staging of a [ROWS x HD] block of a row-major matrix (row stride ld elements): 16-byte chunks,
 // consecutive lanes take consecutive chunks of a row.  NCH chunks per thread (256 threads).
 template <int HD, int ROWS>
@@ -115,7 +123,9 @@ __global__ __launch_bounds__(256, 2) void k_flash_fwd(const bf16* __restrict__ q
   constexpr int kKTile = BKV * KS, kVTile = BKV * VS;
   __shared__ __attribute__((aligned(16))) char smem[2 * (kKTile + kVTile)];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lq = lane & 31, hh = lane >> 5;
-  const int qb = gridDim.x - 1 - blockIdx.x, a = blockIdx.y, b = blockIdx.z;
+  // heaviest query blocks first; the blocks of a head, then the heads of a sequence, are numbered together
+  const int nqb = (T + 127) / 128, wg = xcd_major(blockIdx.x, gridDim.x);
+  const int qb = nqb - 1 - wg % nqb, a = (wg / nqb) % H, b = wg / (nqb * H);
   const int kvh = a / (H / Hkv);
   const int64_t ld = (int64_t)(H + 2 * Hkv) * HD;
   const bf16* Q = qkv + (int64_t)b * T * ld + a * HD;
@@ -292,7 +302,9 @@ __global__ __launch_bounds__(256, 2) void k_flash_bwd_dq(const bf16* __restrict_
   constexpr int kKTile = BKV * KS, kTTile = BKV * TS;
   __shared__ __attribute__((aligned(16))) char smem[2 * kKTile + kTTile];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lq = lane & 31, hh = lane >> 5;
-  const int qb = gridDim.x - 1 - blockIdx.x, a = blockIdx.y, b = blockIdx.z;
+  // heaviest query blocks first; the blocks of a head, then the heads of a sequence, are numbered together
+  const int nqb = (T + 127) / 128, wg = xcd_major(blockIdx.x, gridDim.x);
+  const int qb = nqb - 1 - wg % nqb, a = (wg / nqb) % H, b = wg / (nqb * H);
   const int kvh = a / (H / Hkv);
   const int64_t ld = (int64_t)(H + 2 * Hkv) * HD;
   const bf16* Q = qkv + (int64_t)b * T * ld + a * HD;
@@ -479,7 +491,9 @@ __global__ __launch_bounds__(256) void k_flash_bwd_dkv(const bf16* __restrict__ 
   __shared__ __attribute__((aligned(1024))) char smem[kRing * kBuf];
   const int tid = threadIdx.x, lane = tid & 63, lk = lane & 31, hh = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int kb = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  // heaviest key blocks (the first) first; the blocks of a kv head are numbered together
+  const int nkb = (T + BK - 1) / BK, wg = xcd_major(blockIdx.x, gridDim.x);
+  const int kb = wg % nkb, kvh = (wg / nkb) % Hkv, b = wg / (nkb * Hkv);
   const int rep = H / Hkv;
   const int64_t ld = (int64_t)(H + 2 * Hkv) * HD;
   const bf16* Kp = qkv + (int64_t)b * T * ld + (H + kvh) * HD;
@@ -721,13 +735,13 @@ __global__ __launch_bounds__(256) void k_flash_bwd_dkv(const bf16* __restrict__ 
 
 bool attention_flash_supported(int B, int T, int H, int Hkv, int hd) {
   // one sequence's rows of qkv, and its lse block, are addressed with 31-bit byte offsets
-  return (hd == 64 || hd == 128) && B >= 1 && T >= 1 && B <= 65535 && H <= 65535 && H % Hkv == 0 &&
+  return (hd == 64 || hd == 128) && B >= 1 && T >= 1 && H % Hkv == 0 && (int64_t)((T + 127) / 128) * H * B < (1ll << 31) &&
          (int64_t)T * (H + 2 * Hkv) * hd * 2 < (1ll << 31) && (int64_t)T * H * 4 < (1ll << 31);
 }
 
 void attention_flash_fwd(hipStream_t s, int B, int T, int H, int Hkv, int hd, const void* qkv, void* o, float* lse) {
   const float sl2 = kLog2e / sqrtf((float)hd);
-  dim3 grid((T + 127) / 128, H, B);
+  dim3 grid((unsigned)(((T + 127) / 128) * H * B));
   if (hd == 128)
     hipLaunchKernelGGL(k_flash_fwd<128>, grid, dim3(256), 0, s, (const bf16*)qkv, (bf16*)o, lse, T, H, Hkv, sl2);
   else
@@ -738,7 +752,7 @@ void attention_flash_bwd(hipStream_t s, int B, int T, int H, int Hkv, int hd, co
                          const float* lse, const void* do_, void* dqkv, float* delta) {
   const float scale = 1.0f / sqrtf((float)hd);
   const int64_t items = (int64_t)B * T * H;
-  dim3 gq((T + 127) / 128, H, B), gk((T + 127) / 128, Hkv, B);
+  dim3 gq((unsigned)(((T + 127) / 128) * H * B)), gk((unsigned)(((T + 127) / 128) * Hkv * B));
   // algorithmic flops of the backward pass: four products (dV, dP, dQ, dK) over the causal half;
   // dQ is credited to its kernel, the other three to the dK/dV kernel (the recomputed scores are not counted)
   const double unit = (double)B * H * (double)T * (T + 1) * hd;
