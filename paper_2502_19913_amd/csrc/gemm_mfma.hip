@@ -16,8 +16,10 @@
 //
 //   op 0  C[M,N]  = A[M,K] B[N,K]^T (+R)   A, B k-contiguous
 //   op 1  C[M,N]  = A[M,K] B[K,N]          B k-strided
-//   op 2  C[M,N] += A[K,M]^T B[K,N]        both k-strided; float output; K may be split over
-//                                          workgroups (atomic accumulation) when the output has few tiles
+//   op 2  C[M,N] += A[K,M]^T B[K,N]        both k-strided; float output, added atomically: the k-steps
+//                                          of all tiles are dealt out in equal runs, one per CU, whatever
+//                                          the number of tiles (a weight gradient has few tiles and a
+//                                          long reduction)
 //
 // For bf16 outputs the MFMA is issued with the tile of B as its row operand and the tile of A as its
 // column operand, so a lane's accumulator holds 4 consecutive output columns of one output row; they go
@@ -119,26 +121,39 @@ __device__ __forceinline__ bf16x8 read_frag(const char* tile, int row_base, int 
 template <int OP, bool KMASK>
 __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ B,
                                                         void* __restrict__ Cv, const bf16* __restrict__ Rr, int M,
-                                                        int N, int K, int tiles_m, int tiles_n, int ksplit) {
+                                                        int N, int K, int tiles_m, int tiles_n) {
   constexpr bool AS = OP == 2, BS = OP != 0;   // which operands are k-strided
   __shared__ __attribute__((aligned(16))) char smem[kLdsBytes];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 2, wn = wave & 3;
 
-  // ---- which tile: ids that share an XCD (id mod 8) get consecutive tiles; tiles run down M first
-  // inside bands of 8 tile columns so that neighbours share B panels and reuse A panels
+  // ---- the work of this workgroup.  OP 0/1: one output tile, the whole reduction.  OP 2: the k-steps of
+  // all tiles form one sequence (tile-major), cut into gridDim.x equal runs; a run covers the end of
+  // one tile, whole tiles, the start of another, and every piece is added to the output atomically, so
+  // the workgroups finish together whatever the number of tiles.
+  // Ids that share an XCD (id mod 8) get consecutive tiles (runs); tiles run down M first inside bands
+  // of 8 tile columns so that neighbours share B panels and reuse A panels.
   const int tiles = tiles_m * tiles_n;
   int id = blockIdx.x;
-  const int per_xcd = tiles / 8;
-  if (id < per_xcd * 8) id = (id & 7) * per_xcd + (id >> 3);
+  {
+    const int n_ids = gridDim.x, per = n_ids / 8, rem = n_ids % 8, x = id % 8;
+    id = x * per + min(x, rem) + id / 8;
+  }
+  const int ksteps = (K + BK - 1) / BK;
+  int64_t u = OP == 2 ? (int64_t)id * tiles * ksteps / gridDim.x : (int64_t)id * ksteps;
+  const int64_t u_end = OP == 2 ? (int64_t)(id + 1) * tiles * ksteps / gridDim.x : u + ksteps;
+  while (u < u_end) {
+  const int tile = (int)(u / ksteps), ks0 = (int)(u - (int64_t)tile * ksteps);
+  const int ks1 = (int)min((int64_t)ksteps, ks0 + (u_end - u));
+  u += ks1 - ks0;
   constexpr int kBand = 8;
-  const int band = id / (kBand * tiles_m);
+  const int band = tile / (kBand * tiles_m);
   const int band_w = min(kBand, tiles_n - band * kBand);
-  const int in_band = id - band * kBand * tiles_m;
+  const int in_band = tile - band * kBand * tiles_m;
   const int tm = in_band / band_w, tn = band * kBand + in_band % band_w;
   const int m0 = tm * BM, n0 = tn * BN;
-  const int kb = blockIdx.y * ksplit, kend = min(K, kb + ksplit);
-  const int nk = (kend - kb + BK - 1) / BK;
+  const int kb = ks0 * BK, kend = min(K, ks1 * BK);
+  const int nk = ks1 - ks0;
 
   Operand<AS> opa;
   Operand<BS> opb;
@@ -214,10 +229,9 @@ __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__
   const int lm = lane & 31, hh = lane >> 5;
   if (OP == 2) {
     // float output, accumulated in place.  Here the tile of A is the MFMA's row operand: accumulator r of
-    // lane l is output row (r/4)*8 + (l/32)*4 + r%4, column l%32, so a wavefront's access covers 128
-    // contiguous bytes of two rows (coalesced atomics when K is split).
+    // lane l is output row (r/4)*8 + (l/32)*4 + r%4, column l%32, so a wavefront's atomic covers 128
+    // contiguous bytes of two rows.
     float* C = reinterpret_cast<float*>(Cv);
-    const bool atomic = gridDim.y > 1;
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -228,7 +242,7 @@ __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__
           const int row = m0 + wm * 128 + j * 32 + (r >> 2) * 8 + hh * 4 + (r & 3);
           if (row < M && col < N) {
             float* p = C + (int64_t)row * N + col;
-            if (atomic) unsafeAtomicAdd(p, acc[j][i][r]); else *p += acc[j][i][r];
+            unsafeAtomicAdd(p, acc[j][i][r]);
           }
         }
       }
@@ -272,9 +286,20 @@ __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__
       }
     }
   }
+  }  // next piece of the run
 }
 
 inline bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+int cu_count() {
+  static int n = 0;
+  if (!n) {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) n = v;
+    else n = 256;
+  }
+  return n;
+}
 
 }  // namespace
 
@@ -298,22 +323,19 @@ void gemm_mfma(hipStream_t s, int op, int64_t M, int64_t N, int64_t K, const voi
                const void* R) {
   const int tm = (int)((M + BM - 1) / BM), tn = (int)((N + BN - 1) / BN);
   const int tiles = tm * tn;
-  int splits = 1;
+  int wgs = tiles;
   if (op == 2) {
-    // few output tiles and a long reduction: cut K so that about two rounds of workgroups fill 256 CUs
-    const int ksteps = (int)((K + BK - 1) / BK);
-    splits = std::max(1, std::min((512 + tiles - 1) / tiles, ksteps / 8));
-    splits = std::min(splits, 64);
+    // one run of k-steps per CU, but no run shorter than 4 steps
+    const int64_t units = (int64_t)tiles * ((K + BK - 1) / BK);
+    wgs = (int)std::max<int64_t>(1, std::min<int64_t>(cu_count(), units / 4));
   }
-  int ksplit = (int)(((K + splits - 1) / splits + BK - 1) / BK * BK);
-  splits = (int)((K + ksplit - 1) / ksplit);
-  dim3 grid(tiles, splits);
+  dim3 grid(wgs);
   const bf16* a = (const bf16*)A;
   const bf16* b = (const bf16*)B;
   const bf16* r = (const bf16*)R;
   const bool kmask = K % BK != 0;
 #define SP_LAUNCH(OP, KM) \
-  hipLaunchKernelGGL((k_gemm_mfma<OP, KM>), grid, dim3(kThreads), 0, s, a, b, C, r, (int)M, (int)N, (int)K, tm, tn, ksplit)
+  hipLaunchKernelGGL((k_gemm_mfma<OP, KM>), grid, dim3(kThreads), 0, s, a, b, C, r, (int)M, (int)N, (int)K, tm, tn)
   if (op == 0) { if (kmask) SP_LAUNCH(0, true); else SP_LAUNCH(0, false); }
   else if (op == 1) { if (kmask) SP_LAUNCH(1, true); else SP_LAUNCH(1, false); }
   else SP_LAUNCH(2, false);
