@@ -458,10 +458,10 @@ __device__ __forceinline__ u32x4 make_desc(const void* p, uint32_t bytes) {
   return d;
 }
 __device__ __forceinline__ void load_to_lds16(u32x4 desc, lds_ptr lds, uint32_t voff) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds), "v"(voff), "s"(desc) : "memory", "m0");
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds), "v"(voff), "s"(desc) : "memory");
 }
 __device__ __forceinline__ void load_to_lds4(u32x4 desc, lds_ptr lds, uint32_t voff) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds" ::"s"(lds), "v"(voff), "s"(desc) : "memory", "m0");
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds" ::"s"(lds), "v"(voff), "s"(desc) : "memory");
 }
 
 template <int HD>

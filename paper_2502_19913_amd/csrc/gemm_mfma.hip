@@ -1,18 +1,20 @@
 // bf16 matrix products on the CDNA4 matrix cores (v_mfma_f32_32x32x16_bf16), float accumulation.
 //
 // One workgroup of 8 wavefronts owns a 256x256 tile of the output and walks the reduction
-// dimension in steps of 64.  Operand tiles are staged global -> registers -> LDS with buffer loads
-// (the hardware range check returns zero past the end of an operand, so ragged edges need no
-// branches) two steps ahead of the MFMAs, into two LDS buffers (147 KB of the CU's 160 KB); one
-// barrier per step.
+// dimension in steps of 64.  Operand tiles go from memory straight into LDS (buffer loads with the LDS
+// modifier: no staging registers, no LDS stores; the hardware range check returns zero past the end
+// of an operand, so ragged edges need no branches), one step ahead of the MFMAs, into two stages of
+// 64 KB; one barrier per step.
 //
-// LDS layouts, chosen so that every fragment read is conflict free and every global access is a
-// full 16-byte chunk of a contiguous run:
-//   k-contiguous operand (memory [row][k]): LDS [row][64 k] padded to 144 B; a lane's MFMA fragment
-//     (8 consecutive k of one row) is one ds_read_b128.
-//   k-strided operand (memory [k][x]):      LDS [64 k][256 x] padded to 576 B, copied as is; the
-//     fragment is gathered by two ds_read_b64_tr_b16 (the LDS transpose read: within 16 lanes,
-//     lane i receives element i%4 of the 8-byte pieces addressed by lanes i/4, i/4+4, i/4+8, i/4+12).
+// LDS layouts.  A load instruction fills 1 KiB of LDS in lane order, so tiles are unpadded and the
+// 16-byte chunks of a row are permuted by an XOR with bits of the row number (see Operand), which
+// makes every fragment read conflict free while every global access stays a full 16-byte chunk of a
+// contiguous run:
+//   k-contiguous operand (memory [row][k]): LDS [256 rows][64 k]; a lane's MFMA fragment (8 consecutive
+//     k of one row) is one ds_read_b128.
+//   k-strided operand (memory [k][x]):      LDS [64 k][256 x]; the fragment is gathered by two
+//     ds_read_b64_tr_b16 (the LDS transpose read: within 16 lanes, lane i receives element i%4 of the
+//     8-byte pieces addressed by lanes i/4, i/4+4, i/4+8, i/4+12).
 //
 //   op 0  C[M,N]  = A[M,K] B[N,K]^T (+R)   A, B k-contiguous
 //   op 1  C[M,N]  = A[M,K] B[K,N]          B k-strided
@@ -42,76 +44,86 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int kThreads = 512;
-constexpr int kRowBytes = 144;                  // k-contiguous tile: 64 bf16 + 16 bytes of padding per row
-constexpr int kKRowBytes = 576;                 // k-strided tile: 256 bf16 + 64 bytes of padding per k
-constexpr int kTileBytes = 256 * kRowBytes;     // = 64 * kKRowBytes
-constexpr int kLdsBytes = 4 * kTileBytes;       // A and B, two buffers
+constexpr int kTileBytes = 256 * BK * 2;        // one operand tile, either layout, unpadded
+constexpr int kStageBytes = 2 * kTileBytes;     // A and B
 constexpr int kCRowBytes = 528;                 // output staging: 256 bf16 + 16 bytes
-static_assert(64 * kKRowBytes == kTileBytes, "both tile layouts have the same footprint");
-static_assert(256 * kCRowBytes <= kLdsBytes, "output staging fits in the operand buffers");
+constexpr int kLdsBytes = 256 * kCRowBytes;     // >= two stages
+static_assert(2 * kStageBytes <= kLdsBytes, "two stages fit under the output staging");
 
-// 16 bytes at byte offset voff; zero if voff is at or past the end of the buffer
-__device__ __forceinline__ uint4 bload(rsrc_t rsrc, uint32_t voff) {
-  i32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)voff, 0, 0);
-  return make_uint4((uint32_t)v[0], (uint32_t)v[1], (uint32_t)v[2], (uint32_t)v[3]);
+// Buffer loads with the LDS modifier, written as assembly so that the compiler's wait insertion does not
+// see them (it would make the first LDS read after each of them wait for it).  One instruction copies
+// 64 x 16 bytes from the lanes' buffer offsets to LDS at lds .. lds + 1024 in lane order; an offset at or
+// past the descriptor's size delivers zeros.  Counted by vmcnt like any load.
+typedef __attribute__((address_space(3))) void* lds_ptr;
+__device__ __forceinline__ u32x4 make_desc(const void* p, uint32_t bytes) {
+  const uint64_t a = (uint64_t)p;
+  u32x4 d = {(uint32_t)a, (uint32_t)(a >> 32) & 0xffffu, bytes, 0x00020000u};
+  return d;
 }
+__device__ __forceinline__ void load_to_lds16(u32x4 desc, lds_ptr lds, uint32_t voff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds), "v"(voff), "s"(desc) : "memory");
+}
+constexpr uint32_t kPastEnd = 0x80000000u;      // operands are smaller than this (checked by the caller)
 
-// One operand's share of the staging for one thread: 4 chunks of 16 bytes.
+// One operand's share of the tile loads for one wavefront: 4 instructions of 1 KiB per step.
+// Instruction j fills the tile's 16-byte chunks (8j + wave) * 64 + lane.
+//   k-contiguous tile: [256 rows][64 k], 8 chunks per row; the chunk at position p of a row holds the row's
+//     chunk p ^ ((row >> 1) & 7): the 16 rows a ds_read_b128 touches then fall in 16 different bank groups.
+//   k-strided tile: [64 k][256 x], 32 chunks per k row; position p of k row k holds chunk p ^ ((k & 3) << 2):
+//     the 4 k rows x 4 chunks a transpose read touches fall in 16 different bank groups.
+// The permutation is applied on the memory side: a lane fetches the chunk that belongs at its position.
 template <bool KSTRIDED>
 struct Operand {
-  rsrc_t rsrc;
-  uint32_t voff0;      // byte offset of this thread's chunk 0 at k = 0
-  uint32_t chunk_step; // distance between the thread's consecutive chunks
+  u32x4 desc;
+  uint32_t voff[4];    // byte offset of the lane's chunk for k0 = 0, per instruction
   uint32_t k_step;     // byte distance of one k element
-  int kc8;             // k-contiguous: first k of the thread's chunk inside a step
-  int lds_off;         // byte offset of chunk 0 in the LDS tile
+  int kc8;             // k-contiguous: first k of the lane's chunk inside a step
   // ld: leading dimension (elements); origin: first tile row (k-contiguous) or first x (k-strided)
-  __device__ __forceinline__ void init(const bf16* X, uint32_t bytes, int ld, int origin, int tid) {
-    rsrc = make_rsrc(X, bytes);
-    if (KSTRIDED) {
-      const int krow = tid >> 5, xc = tid & 31;          // chunk c = tid + 512 i: k row c / 32, x chunk c % 32
-      voff0 = ((uint32_t)krow * ld + origin + xc * 8) * 2u;
-      chunk_step = 16u * ld * 2u;
-      k_step = (uint32_t)ld * 2u;
-      kc8 = 0;
-      lds_off = krow * kKRowBytes + xc * 16;
-    } else {
-      const int row = tid >> 3, kc = tid & 7;            // chunk c = tid + 512 i: row c / 8, k chunk c % 8
-      voff0 = ((uint32_t)(origin + row) * ld + kc * 8) * 2u;
-      chunk_step = 64u * ld * 2u;
-      k_step = 2u;
-      kc8 = kc * 8;
-      lds_off = row * kRowBytes + kc * 16;
+  __device__ __forceinline__ void init(const bf16* X, uint32_t bytes, int ld, int origin, int wave, int lane) {
+    desc = make_desc(X, bytes);
+    kc8 = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int q = (8 * j + wave) * 64 + lane;
+      if (KSTRIDED) {
+        const int krow = q >> 5, pos = q & 31, c = pos ^ ((krow & 3) << 2);
+        voff[j] = ((uint32_t)krow * ld + origin + c * 8) * 2u;
+      } else {
+        const int row = q >> 3, pos = q & 7, c = pos ^ ((row >> 1) & 7);
+        voff[j] = ((uint32_t)(origin + row) * ld + c * 8) * 2u;
+        kc8 = c * 8;   // the same for every j: it depends on lane and wave & 1 only
+      }
     }
+    k_step = KSTRIDED ? (uint32_t)ld * 2u : 2u;
   }
   // KMASK (k-contiguous only): chunks whose k is at or past kend read as zero
   template <bool KMASK>
-  __device__ __forceinline__ void load(int k0, int kend, uint4 (&reg)[4]) const {
-    const uint32_t base = voff0 + (uint32_t)k0 * k_step;
+  __device__ __forceinline__ void load(int k0, int kend, char* tile, int wave) const {
     const bool dead = KMASK && !KSTRIDED && (k0 + kc8 >= kend);
+    const uint32_t add = (uint32_t)k0 * k_step;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) reg[i] = bload(rsrc, dead ? 0xffffffffu : base + i * chunk_step);
-  }
-  __device__ __forceinline__ void store(char* tile, const uint4 (&reg)[4]) const {
-    constexpr int step = KSTRIDED ? 16 * kKRowBytes : 64 * kRowBytes;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4*>(tile + lds_off + i * step) = reg[i];
+    for (int j = 0; j < 4; ++j) load_to_lds16(desc, (lds_ptr)(tile + (8 * j + wave) * 1024), dead ? kPastEnd : voff[j] + add);
   }
 };
 
-// MFMA fragment of tile row `row` (0..255) for k-step ks (16 k): 8 consecutive k, starting at
-// ks*16 + (lane/32)*8, of that row.
+// MFMA fragment of tile row `row_base + lane % 32` for k-step ks (16 k): 8 consecutive k, starting at
+// ks*16 + (lane/32)*8.  row_base is a multiple of 32.
 template <bool KSTRIDED>
 __device__ __forceinline__ bf16x8 read_frag(const char* tile, int row_base, int ks, int lane) {
   if (!KSTRIDED) {
-    return *reinterpret_cast<const bf16x8*>(tile + (row_base + (lane & 31)) * kRowBytes + ks * 32 + (lane >> 5) * 16);
+    const int lr = lane & 31, hh = lane >> 5;
+    // chunk 2 ks + hh permuted by the row's key; ks enters by XOR with ks * 32
+    const int lane_off = lr * 128 + ((hh ^ ((lr >> 1) & 7)) << 4);
+    return *reinterpret_cast<const bf16x8*>(tile + row_base * 128 + (lane_off ^ (ks * 32)));
   } else {
-    // group of 16 lanes = 16 consecutive x; lane s of the group addresses k row s/4, x piece s%4
-    const int g16 = (lane >> 4) & 1, hh = lane >> 5, s = lane & 15;
-    const char* p = tile + (ks * 16 + hh * 8 + (s >> 2)) * kKRowBytes + (row_base + g16 * 16 + (s & 3) * 4) * 2;
+    // group of 16 lanes = 16 consecutive x; lane s of the group addresses k row s/4, x piece s%4:
+    // k row ks*16 + hh*8 + i (and + 4), chunk row_base/8 + 2 g16 + (s%4)/2, permuted by i << 2
+    const int g16 = (lane >> 4) & 1, hh = lane >> 5, s = lane & 15, i = s >> 2;
+    const int lane_off = (hh * 8 + i) * 512 + (((i << 2) | (g16 * 2 + ((s & 3) >> 1))) << 4) + (s & 1) * 8;
+    const char* p = tile + ks * 16 * 512 + (lane_off ^ (row_base * 2));   // row_base * 2 = chunk bits 2.. : multiple of 64
     typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
     s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
-    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * kKRowBytes));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * 512));
     typedef __attribute__((ext_vector_type(8))) short s16x8;
     s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
     return __builtin_bit_cast(bf16x8, v);
@@ -123,8 +135,9 @@ __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__
                                                         void* __restrict__ Cv, const bf16* __restrict__ Rr, int M,
                                                         int N, int K, int tiles_m, int tiles_n) {
   constexpr bool AS = OP == 2, BS = OP != 0;   // which operands are k-strided
-  __shared__ __attribute__((aligned(16))) char smem[kLdsBytes];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  __shared__ __attribute__((aligned(1024))) char smem[kLdsBytes];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 2, wn = wave & 3;
 
   // ---- the work of this workgroup.  OP 0/1: one output tile, the whole reduction.  OP 2: the k-steps of
@@ -157,8 +170,8 @@ __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__
 
   Operand<AS> opa;
   Operand<BS> opb;
-  opa.init(A, (uint32_t)((size_t)M * K * 2), AS ? M : K, m0, tid);
-  opb.init(B, (uint32_t)((size_t)N * K * 2), BS ? N : K, n0, tid);
+  opa.init(A, (uint32_t)((size_t)M * K * 2), AS ? M : K, m0, wave, lane);
+  opb.init(B, (uint32_t)((size_t)N * K * 2), BS ? N : K, n0, wave, lane);
 
   // acc[j][i]: MFMA rows = 32 output columns n (i of 2), MFMA columns = 32 output rows m (j of 4)
   f32x16 acc[4][2];
@@ -169,7 +182,6 @@ __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[j][i][r] = 0.f;
 
-  uint4 ra[2][4], rb[2][4];
   auto compute = [&](const char* base) {
     const char* ta = base;
     const char* tb = base + kTileBytes;
@@ -188,40 +200,24 @@ __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__
                               : __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[i], fa[j], acc[j][i], 0, 0, 0);
     }
   };
-  auto gload = [&](int t, uint4 (&xa)[4], uint4 (&xb)[4]) {
-    opa.template load<KMASK>(kb + t * BK, kend, xa);
-    opb.template load<KMASK>(kb + t * BK, kend, xb);
+  // step t of the reduction goes to stage t & 1
+  auto issue = [&](int t) {
+    char* st = smem + (t & 1) * kStageBytes;
+    opa.template load<KMASK>(kb + t * BK, kend, st, wave);
+    opb.template load<KMASK>(kb + t * BK, kend, st + kTileBytes, wave);
   };
-  auto sstore = [&](int t, const uint4 (&xa)[4], const uint4 (&xb)[4]) {
-    char* d = smem + (t & 1) * 2 * kTileBytes;
-    opa.store(d, xa);
-    opb.store(d + kTileBytes, xb);
+  // this wavefront's loads have landed and its LDS reads are done; then the same for the others
+  auto landed_barrier = [&]() {
+    __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (0 << 8));   // vmcnt(0) lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
   };
 
-  // tile t of the reduction waits in register set t & 1 until it is written to LDS buffer t & 1
-  if (nk > 0) {
-    gload(0, ra[0], rb[0]);
-    if (nk > 1) gload(1, ra[1], rb[1]);
-    sstore(0, ra[0], rb[0]);
-  }
-  __syncthreads();
-  int kt = 0;
-  for (; kt + 3 < nk; kt += 2) {   // steady state: no conditionals, so outstanding loads can be counted
-    gload(kt + 2, ra[0], rb[0]);
-    compute(smem);
-    sstore(kt + 1, ra[1], rb[1]);
-    __syncthreads();
-    gload(kt + 3, ra[1], rb[1]);
-    compute(smem + 2 * kTileBytes);
-    sstore(kt + 2, ra[0], rb[0]);
-    __syncthreads();
-  }
-  for (; kt < nk; ++kt) {          // the last (up to three) steps
-    const bool odd = kt & 1;
-    if (kt + 2 < nk) { if (odd) gload(kt + 2, ra[1], rb[1]); else gload(kt + 2, ra[0], rb[0]); }
-    compute(smem + (kt & 1) * 2 * kTileBytes);
-    if (kt + 1 < nk) { if (odd) sstore(kt + 1, ra[0], rb[0]); else sstore(kt + 1, ra[1], rb[1]); }
-    __syncthreads();
+  issue(0);
+  landed_barrier();
+  for (int kt = 0; kt < nk; ++kt) {
+    if (kt + 1 < nk) issue(kt + 1);   // into the stage every wavefront left before the last barrier
+    compute(smem + (kt & 1) * kStageBytes);
+    landed_barrier();
   }
 
   // ---- epilogue.  Accumulator r of lane l: output row m = lane%32, output column n = (r/4)*8 + (l/32)*4 + r%4
@@ -306,8 +302,8 @@ int cu_count() {
 bool gemm_mfma_supported(int op, int64_t M, int64_t N, int64_t K, const void* A, const void* B, const void* C,
                          const void* R) {
   if (M < 1 || N < 1 || K < 1) return false;
-  // buffer descriptors address up to 4 GiB per operand with 32-bit offsets
-  if (M * K * 2 >= ((int64_t)1 << 32) || N * K * 2 >= ((int64_t)1 << 32)) return false;
+  // 31-bit byte offsets into each operand
+  if (M * K * 2 >= ((int64_t)1 << 31) || N * K * 2 >= ((int64_t)1 << 31)) return false;
   if (!al16(A) || !al16(B) || !al16(C) || (R && !al16(R))) return false;
   if (((M + BM - 1) / BM) * ((N + BN - 1) / BN) > (1 << 24)) return false;
   if (N % 8) return false;                      // 16-byte output chunks
