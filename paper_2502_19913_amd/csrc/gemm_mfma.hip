@@ -140,10 +140,10 @@ __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 2, wn = wave & 3;
 
-  // ---- the work of this workgroup.  OP 0/1: one output tile, the whole reduction.  OP 2: the k-steps of
-  // all tiles form one sequence (tile-major), cut into gridDim.x equal runs; a run covers the end of
-  // one tile, whole tiles, the start of another, and every piece is added to the output atomically, so
-  // the workgroups finish together whatever the number of tiles.
+  // ---- the work of this workgroup: a sequence of pieces, each a range of k-steps of one output tile.
+  // OP 0/1: whole tiles id, id + gridDim.x, ...: the launch has as many workgroups as make its rounds of
+  // tiles equally full.  OP 2: the k-steps of all tiles form one sequence (tile-major), cut into gridDim.x
+  // equal runs (normally a whole number of runs per tile); every piece is added to the output atomically.
   // Ids that share an XCD (id mod 8) get consecutive tiles (runs); tiles run down M first inside bands
   // of 8 tile columns so that neighbours share B panels and reuse A panels.
   const int tiles = tiles_m * tiles_n;
@@ -154,11 +154,11 @@ __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__
   }
   const int ksteps = (K + BK - 1) / BK;
   int64_t u = OP == 2 ? (int64_t)id * tiles * ksteps / gridDim.x : (int64_t)id * ksteps;
-  const int64_t u_end = OP == 2 ? (int64_t)(id + 1) * tiles * ksteps / gridDim.x : u + ksteps;
+  const int64_t u_end = OP == 2 ? (int64_t)(id + 1) * tiles * ksteps / gridDim.x : (int64_t)tiles * ksteps;
   while (u < u_end) {
   const int tile = (int)(u / ksteps), ks0 = (int)(u - (int64_t)tile * ksteps);
-  const int ks1 = (int)min((int64_t)ksteps, ks0 + (u_end - u));
-  u += ks1 - ks0;
+  const int ks1 = OP == 2 ? (int)min((int64_t)ksteps, ks0 + (u_end - u)) : ksteps;
+  u += OP == 2 ? (int64_t)(ks1 - ks0) : (int64_t)gridDim.x * ksteps;
   constexpr int kBand = 8;
   const int band = tile / (kBand * tiles_m);
   const int band_w = min(kBand, tiles_n - band * kBand);
@@ -281,8 +281,9 @@ __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__
         }
       }
     }
+    __syncthreads();   // the staging area becomes the next piece's operand stages
   }
-  }  // next piece of the run
+  }  // next piece
 }
 
 inline bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
@@ -319,11 +320,26 @@ void gemm_mfma(hipStream_t s, int op, int64_t M, int64_t N, int64_t K, const voi
                const void* R) {
   const int tm = (int)((M + BM - 1) / BM), tn = (int)((N + BN - 1) / BN);
   const int tiles = tm * tn;
-  int wgs = tiles;
+  // The chip delivers about the same aggregate rate with two thirds of its CUs busy as with all of them
+  // (the kernel is bound by what the L2s and the power budget give), but a nearly empty round is lost time.
+  const int cus = cu_count();
+  int wgs;
   if (op == 2) {
-    // one run of k-steps per CU, but no run shorter than 4 steps
-    const int64_t units = (int64_t)tiles * ((K + BK - 1) / BK);
-    wgs = (int)std::max<int64_t>(1, std::min<int64_t>(cu_count(), units / 4));
+    // a whole number s of runs per tile, so that the runs of neighbouring tiles walk the same k range
+    // together: the smallest s whose last round of s * tiles workgroups is at least 0.65 full
+    const int ksteps = (int)((K + BK - 1) / BK);
+    int s_best = 1;
+    for (int sp = 1; sp <= 8 && ksteps / sp >= 8; ++sp) {
+      const int64_t w = (int64_t)tiles * sp;
+      const int64_t last = w % cus;
+      s_best = sp;
+      if (last == 0 || last * 100 >= (int64_t)cus * 65 || w >= 6 * (int64_t)cus) break;
+    }
+    wgs = tiles * s_best;
+  } else {
+    // equally full rounds: ceil(tiles / rounds) workgroups, each taking every wgs-th tile
+    const int rounds = (tiles + cus - 1) / cus;
+    wgs = (tiles + rounds - 1) / rounds;
   }
   dim3 grid(wgs);
   const bf16* a = (const bf16*)A;
