@@ -73,6 +73,18 @@ __device__ __forceinline__ int xcd_major(int L, int N) {
   return x * per + min(x, rem) + L / 8;
 }
 
+// Gradient of a rotated vector -> gradient of the vector before the rotation, for 4 consecutive columns
+// col..col+3 (two pairs) of the head-dimension at position pos: the transpose of the rotation, i.e. a turn
+// by the opposite angle.  tab holds (cos, sin) per (position, pair).
+__device__ __forceinline__ void unrotate4(float (&v)[4], const float* __restrict__ tab, int pos, int hd, int col) {
+  const float4 cs = *reinterpret_cast<const float4*>(tab + ((int64_t)pos * (hd / 2) + col / 2) * 2);
+  const float a0 = v[0], b0 = v[1], a1 = v[2], b1 = v[3];
+  v[0] = a0 * cs.x + b0 * cs.y;
+  v[1] = b0 * cs.x - a0 * cs.y;
+  v[2] = a1 * cs.z + b1 * cs.w;
+  v[3] = b1 * cs.z - a1 * cs.w;
+}
+
 // ---- staging of a [ROWS x HD] block of a row-major matrix (row stride ld elements): 16-byte chunks,
 // consecutive lanes take consecutive chunks of a row.  NCH chunks per thread (256 threads).
 template <int HD, int ROWS>
@@ -295,7 +307,8 @@ __global__ __launch_bounds__(256) void k_flash_delta(const bf16* __restrict__ o,
 template <int HD>
 __global__ __launch_bounds__(256, 2) void k_flash_bwd_dq(const bf16* __restrict__ qkv, const bf16* __restrict__ dO,
                                                          const float* __restrict__ lse, const float* __restrict__ delta,
-                                                         bf16* __restrict__ dqkv, int T, int H, int Hkv, float scale) {
+                                                         bf16* __restrict__ dqkv, int T, int H, int Hkv, float scale,
+                                                         const float* __restrict__ rope_tab) {
   constexpr int BQ = 128, BKV = 64;
   constexpr int KS = HD * 2 + 16;   // K and V tiles [key][hd]
   constexpr int TS = HD * 2 + 64;   // second copy of K, [key][hd], strided for the transpose read
@@ -409,8 +422,10 @@ __global__ __launch_bounds__(256, 2) void k_flash_bwd_dq(const bf16* __restrict_
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         uint2 w;
-        w.x = pack_bf16(dq[c][4 * g] * scale, dq[c][4 * g + 1] * scale);
-        w.y = pack_bf16(dq[c][4 * g + 2] * scale, dq[c][4 * g + 3] * scale);
+        float q4[4] = {dq[c][4 * g] * scale, dq[c][4 * g + 1] * scale, dq[c][4 * g + 2] * scale, dq[c][4 * g + 3] * scale};
+        if (rope_tab) unrotate4(q4, rope_tab, q, HD, c * 32 + g * 8 + hh * 4);
+        w.x = pack_bf16(q4[0], q4[1]);
+        w.y = pack_bf16(q4[2], q4[3]);
         *reinterpret_cast<uint2*>(row + c * 32 + g * 8 + hh * 4) = w;
       }
   }
@@ -484,10 +499,11 @@ struct DkvGeom {
 template <int HD>
 __global__ __launch_bounds__(256) void k_flash_bwd_dkv(const bf16* __restrict__ qkv, const bf16* __restrict__ dO,
                                                        const float* __restrict__ lse, const float* __restrict__ delta,
-                                                       bf16* __restrict__ dqkv, int T, int H, int Hkv, float scale) {
+                                                       bf16* __restrict__ dqkv, int T, int H, int Hkv, float scale,
+                                                       const float* __restrict__ rope_tab) {
   typedef DkvGeom<HD> G;
   constexpr int BK = 128, BQ = G::BQ, NK = G::NK, NC = G::NC, RB = G::RB, CPR = G::CPR, NJ = G::NJ;
-  constexpr int kTile = G::kTile, kDO = G::kDO, kL = G::kL, kD = G::kD, kBuf = G::kBuf, kRing = G::kRing, kDepth = G::kDepth;
+  constexpr int kDO = G::kDO, kL = G::kL, kD = G::kD, kBuf = G::kBuf, kRing = G::kRing, kDepth = G::kDepth;
   __shared__ __attribute__((aligned(1024))) char smem[kRing * kBuf];
   const int tid = threadIdx.x, lane = tid & 63, lk = lane & 31, hh = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -721,8 +737,10 @@ __global__ __launch_bounds__(256) void k_flash_bwd_dkv(const bf16* __restrict__ 
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         uint2 w;
-        w.x = pack_bf16(dk[c][4 * g] * ks, dk[c][4 * g + 1] * ks);
-        w.y = pack_bf16(dk[c][4 * g + 2] * ks, dk[c][4 * g + 3] * ks);
+        float k4[4] = {dk[c][4 * g] * ks, dk[c][4 * g + 1] * ks, dk[c][4 * g + 2] * ks, dk[c][4 * g + 3] * ks};
+        if (rope_tab) unrotate4(k4, rope_tab, key, HD, c * 32 + g * 8 + hh * 4);
+        w.x = pack_bf16(k4[0], k4[1]);
+        w.y = pack_bf16(k4[2], k4[3]);
         *reinterpret_cast<uint2*>(krow + c * 32 + g * 8 + hh * 4) = w;
         w.x = pack_bf16(dv[c][4 * g], dv[c][4 * g + 1]);
         w.y = pack_bf16(dv[c][4 * g + 2], dv[c][4 * g + 3]);
@@ -749,7 +767,7 @@ void attention_flash_fwd(hipStream_t s, int B, int T, int H, int Hkv, int hd, co
 }
 
 void attention_flash_bwd(hipStream_t s, int B, int T, int H, int Hkv, int hd, const void* qkv, const void* o,
-                         const float* lse, const void* do_, void* dqkv, float* delta) {
+                         const float* lse, const void* do_, void* dqkv, float* delta, const float* rope_tab) {
   const float scale = 1.0f / sqrtf((float)hd);
   const int64_t items = (int64_t)B * T * H;
   dim3 gq((unsigned)(((T + 127) / 128) * H * B)), gk((unsigned)(((T + 127) / 128) * Hkv * B));
@@ -767,18 +785,18 @@ void attention_flash_bwd(hipStream_t s, int B, int T, int H, int Hkv, int hd, co
   pi = prof_start(PROF_ATTN_DQ, s);
   if (hd == 128)
     hipLaunchKernelGGL(k_flash_bwd_dq<128>, gq, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)do_, lse, delta,
-                       (bf16*)dqkv, T, H, Hkv, scale);
+                       (bf16*)dqkv, T, H, Hkv, scale, rope_tab);
   else
     hipLaunchKernelGGL(k_flash_bwd_dq<64>, gq, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)do_, lse, delta,
-                       (bf16*)dqkv, T, H, Hkv, scale);
+                       (bf16*)dqkv, T, H, Hkv, scale, rope_tab);
   prof_stop(pi, s, unit);
   pi = prof_start(PROF_ATTN_DKV, s);
   if (hd == 128)
     hipLaunchKernelGGL(k_flash_bwd_dkv<128>, gk, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)do_, lse, delta,
-                       (bf16*)dqkv, T, H, Hkv, scale);
+                       (bf16*)dqkv, T, H, Hkv, scale, rope_tab);
   else
     hipLaunchKernelGGL(k_flash_bwd_dkv<64>, gk, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)do_, lse, delta,
-                       (bf16*)dqkv, T, H, Hkv, scale);
+                       (bf16*)dqkv, T, H, Hkv, scale, rope_tab);
   prof_stop(pi, s, 3.0 * unit);
 }
 

@@ -239,16 +239,17 @@ int attention_fwd(hipStream_t s, int dtype, int B, int T, int H, int Hkv, int hd
 }
 
 int attention_bwd(hipStream_t s, int dtype, int B, int T, int H, int Hkv, int hd, const void* qkv, const void* o,
-                  const float* lse, const void* do_, void* dqkv, float* delta) {
+                  const float* lse, const void* do_, void* dqkv, float* delta, const float* rope_tab, float rope_theta) {
   int rc = check_attn(B, T, H, Hkv, hd);
   if (rc) return rc;
   if (!qkv || !o || !lse || !do_ || !dqkv || !delta) return fail(SP_EINVAL, "attention: null operand");
   if (dtype == SP_BF16 && attention_flash_supported(B, T, H, Hkv, hd)) {
-    attention_flash_bwd(s, B, T, H, Hkv, hd, qkv, o, lse, do_, dqkv, delta);
+    attention_flash_bwd(s, B, T, H, Hkv, hd, qkv, o, lse, do_, dqkv, delta, rope_tab);   // rotates dq, dk on the way out
   } else {
     const int pi = prof_start(PROF_ATTN_PLAIN, s);
     attention_simple_bwd(s, dtype, B, T, H, Hkv, hd, qkv, o, lse, do_, dqkv, delta);
     prof_stop(pi, s, 4.0 * (double)B * H * (double)T * (T + 1) * hd);
+    if (rope_tab) rope(s, dtype, dqkv, (int64_t)B * T, T, H + Hkv, hd, (H + 2 * Hkv) * hd, rope_theta, -1);
   }
   return SP_OK;
 }

@@ -70,7 +70,7 @@ int64_t head_chunk_rows(const Dims& D, int64_t total_rows) {
 }
 
 struct Carve {
-  size_t arena, t_y, t_d0, t_d1, t_d2, t_da, t_dgu, t_dqkv, t_delta, h_xn, h_rstd, h_logits, h_dxn, pool_a, pool_d,
+  size_t arena, t_y, t_d0, t_d1, t_d2, t_da, t_dgu, t_dqkv, t_delta, rope, h_xn, h_rstd, h_logits, h_dxn, pool_a, pool_d,
       loss_mb, counts, total;
   size_t arena_bytes;
 };
@@ -91,6 +91,7 @@ Carve carve(const sp_cfg& c, int n_mb_max, int n_visits_max) {
   w.t_dgu = take(Rmax * 2 * D.h * D.E);
   w.t_dqkv = take(Rmax * D.nq * D.E);
   w.t_delta = take(Rmax * D.H * sizeof(float));
+  w.rope = take((size_t)D.T * (D.hd / 2) * 2 * sizeof(float));   // cos, sin per (position, pair)
   if (c.has_head) {
     const int64_t ch = head_chunk_rows(D, Rmax);
     w.h_xn = take(ch * D.d * D.E);
@@ -119,6 +120,7 @@ struct sp_ctx {
   hipStream_t stream;
   int n_mb_max, n_visits_max;
   char* base;
+  float* rope_tab;   // inside the workspace, filled at creation
   Carve w;
   size_t arena_top;
   std::vector<Record> records;
@@ -195,6 +197,14 @@ int sp_create(const sp_cfg* cfg, void* hip_stream, int n_mb_max, int n_visits_ma
   if (e != hipSuccess) {
     delete c;
     return fail(SP_ENOMEM, std::string("hipMalloc of the workspace failed: ") + hipGetErrorString(e));
+  }
+  c->rope_tab = (float*)at(c, c->w.rope);
+  rope_table(c->stream, (int)Dims(*cfg).T, (int)Dims(*cfg).hd, cfg->rope_theta, c->rope_tab);
+  e = hipGetLastError();
+  if (e != hipSuccess) {
+    hipFree(c->base);
+    delete c;
+    return hip_fail((int)e, "rope table");
   }
   *out = c;
   return SP_OK;
@@ -276,8 +286,9 @@ int sp_stage_fwd(sp_ctx* ctx, int stage, const void* params, void* act_pool, con
     LayerSaved& ls = rec.layers[l];
     char* y = l + 1 < cfg.layers_per_stage ? rec.layers[l + 1].x : at(ctx, ctx->w.t_y);
     rmsnorm_fwd(s, dt, ls.x, P(ctx, params, w.g1), R, (int)D.d, cfg.rms_eps, ls.xn, ls.rstd1);
-    if ((rc = gemm(s, dt, 0, R, D.nq, D.d, ls.xn, P(ctx, params, w.wqkv), ls.qkv, nullptr))) return rc;
-    rope(s, dt, ls.qkv, R, (int)D.T, (int)(D.H + D.Hkv), (int)D.hd, (int)D.nq, cfg.rope_theta, +1);
+    // q, k, v = xn Wqkv^T, the heads of q and k rotated by their positions
+    const RopeArgs ra = {ctx->rope_tab, (int)D.T, (int)D.hd, (int)((D.H + D.Hkv) * D.hd)};
+    if ((rc = gemm_rope(s, dt, R, D.nq, D.d, ls.xn, P(ctx, params, w.wqkv), ls.qkv, ra, cfg.rope_theta))) return rc;
     if ((rc = attention_fwd(s, dt, Bg, (int)D.T, (int)D.H, (int)D.Hkv, (int)D.hd, ls.qkv, ls.o, ls.lse))) return rc;
     if ((rc = gemm(s, dt, 0, R, D.d, D.d, ls.o, P(ctx, params, w.wo), ls.h, ls.x))) return rc;
     rmsnorm_fwd(s, dt, ls.h, P(ctx, params, w.g2), R, (int)D.d, cfg.rms_eps, ls.hn, ls.rstd2);
@@ -338,9 +349,9 @@ int sp_stage_bwd(sp_ctx* ctx, int stage, const void* params, void* dact_pool, co
     // attention: h = x + o Wo^T
     if ((rc = gemm(s, dt, 2, D.d, D.d, R, dh, ls.o, grads + w.wo, nullptr))) return rc;
     if ((rc = gemm(s, dt, 1, R, D.d, D.d, dh, P(ctx, params, w.wo), t, nullptr))) return rc;
-    if ((rc = attention_bwd(s, dt, Bg, (int)D.T, (int)D.H, (int)D.Hkv, (int)D.hd, ls.qkv, ls.o, ls.lse, t, dqkv, delta)))
+    if ((rc = attention_bwd(s, dt, Bg, (int)D.T, (int)D.H, (int)D.Hkv, (int)D.hd, ls.qkv, ls.o, ls.lse, t, dqkv, delta,
+                            ctx->rope_tab, cfg.rope_theta)))
       return rc;
-    rope(s, dt, dqkv, R, (int)D.T, (int)(D.H + D.Hkv), (int)D.hd, (int)D.nq, cfg.rope_theta, -1);
     if ((rc = gemm(s, dt, 2, D.nq, D.d, R, dqkv, ls.xn, grads + w.wqkv, nullptr))) return rc;
     if ((rc = gemm(s, dt, 1, R, D.d, D.nq, dqkv, P(ctx, params, w.wqkv), t, nullptr))) return rc;
     rmsnorm_bwd(s, dt, t, ls.x, P(ctx, params, w.g1), ls.rstd1, dh, R, (int)D.d, dy, grads + w.g1);

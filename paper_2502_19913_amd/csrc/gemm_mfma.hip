@@ -130,10 +130,11 @@ __device__ __forceinline__ bf16x8 read_frag(const char* tile, int row_base, int 
   }
 }
 
-template <int OP, bool KMASK>
+// ROPE (op 0 only): the leading rope.rot_cols columns of the output are rotated on the way out
+template <int OP, bool KMASK, bool ROPE = false>
 __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ B,
                                                         void* __restrict__ Cv, const bf16* __restrict__ Rr, int M,
-                                                        int N, int K, int tiles_m, int tiles_n) {
+                                                        int N, int K, int tiles_m, int tiles_n, RopeArgs rope) {
   constexpr bool AS = OP == 2, BS = OP != 0;   // which operands are k-strided
   __shared__ __attribute__((aligned(1024))) char smem[kLdsBytes];
   const int tid = threadIdx.x, lane = tid & 63;
@@ -266,7 +267,23 @@ __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__
       if (grow < M && gcol < N) {   // N is a multiple of 8: a chunk is inside or outside as a whole
         uint4 v = *reinterpret_cast<const uint4*>(smem + row * kCRowBytes + nc * 16);
         const int64_t at = (int64_t)grow * N + gcol;
-        if (add) {
+        if (ROPE && gcol < rope.rot_cols) {
+          // 8 columns = 4 pairs of one head (hd is a multiple of 8); their cos, sin are 32 contiguous bytes
+          float x[8];
+          const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) { x[2 * e] = bf16_bits_to_float(wv[e] & 0xffffu); x[2 * e + 1] = bf16_bits_to_float(wv[e] >> 16); }
+          const float4* cs = reinterpret_cast<const float4*>(rope.table) + ((int64_t)(grow % rope.T) * (rope.hd / 2) + (gcol % rope.hd) / 2) / 2;
+          const float4 c01 = cs[0], c23 = cs[1];
+          const float c[4] = {c01.x, c01.z, c23.x, c23.z}, sn[4] = {c01.y, c01.w, c23.y, c23.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float a = x[2 * e], b = x[2 * e + 1];
+            x[2 * e] = a * c[e] - b * sn[e];
+            x[2 * e + 1] = a * sn[e] + b * c[e];
+          }
+          store8(C + at, x);
+        } else if (add) {
           // the sum is formed in float from the accumulator's bf16 rounding; one more rounding on the way out
           float x[8], y[8];
           const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
@@ -317,7 +334,7 @@ bool gemm_mfma_supported(int op, int64_t M, int64_t N, int64_t K, const void* A,
 }
 
 void gemm_mfma(hipStream_t s, int op, int64_t M, int64_t N, int64_t K, const void* A, const void* B, void* C,
-               const void* R) {
+               const void* R, const RopeArgs* rope) {
   const int tm = (int)((M + BM - 1) / BM), tn = (int)((N + BN - 1) / BN);
   const int tiles = tm * tn;
   // The chip delivers about the same aggregate rate with two thirds of its CUs busy as with all of them
@@ -346,11 +363,13 @@ void gemm_mfma(hipStream_t s, int op, int64_t M, int64_t N, int64_t K, const voi
   const bf16* b = (const bf16*)B;
   const bf16* r = (const bf16*)R;
   const bool kmask = K % BK != 0;
-#define SP_LAUNCH(OP, KM) \
-  hipLaunchKernelGGL((k_gemm_mfma<OP, KM>), grid, dim3(kThreads), 0, s, a, b, C, r, (int)M, (int)N, (int)K, tm, tn)
-  if (op == 0) { if (kmask) SP_LAUNCH(0, true); else SP_LAUNCH(0, false); }
-  else if (op == 1) { if (kmask) SP_LAUNCH(1, true); else SP_LAUNCH(1, false); }
-  else SP_LAUNCH(2, false);
+  const RopeArgs ra = rope ? *rope : RopeArgs{nullptr, 1, 8, 0};
+#define SP_LAUNCH(OP, KM, RP) \
+  hipLaunchKernelGGL((k_gemm_mfma<OP, KM, RP>), grid, dim3(kThreads), 0, s, a, b, C, r, (int)M, (int)N, (int)K, tm, tn, ra)
+  if (op == 0 && rope) { if (kmask) SP_LAUNCH(0, true, true); else SP_LAUNCH(0, false, true); }
+  else if (op == 0) { if (kmask) SP_LAUNCH(0, true, false); else SP_LAUNCH(0, false, false); }
+  else if (op == 1) { if (kmask) SP_LAUNCH(1, true, false); else SP_LAUNCH(1, false, false); }
+  else SP_LAUNCH(2, false, false);
 #undef SP_LAUNCH
 }
 

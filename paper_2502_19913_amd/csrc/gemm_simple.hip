@@ -103,4 +103,24 @@ int gemm(hipStream_t s, int dtype, int op, int64_t M, int64_t N, int64_t K, cons
   return SP_OK;
 }
 
+int gemm_rope(hipStream_t s, int dtype, int64_t M, int64_t N, int64_t K, const void* A, const void* B, void* C,
+              const RopeArgs& ra, float rope_theta) {
+  if (M < 0 || N < 0 || K < 0 || ra.hd < 2 || ra.hd % 2 || ra.rot_cols % ra.hd || ra.rot_cols > N || ra.T < 1)
+    return fail(SP_EINVAL, "gemm_rope: bad shape");
+  if ((M > 0 && N > 0) && (!C || (K > 0 && (!A || !B)))) return fail(SP_EINVAL, "gemm_rope: null operand");
+  if (M == 0 || N == 0) return SP_OK;
+  // fused when the matrix-core path takes the product and a 16-byte output chunk never straddles a head
+  const bool fast = dtype == SP_BF16 && ra.table && ra.hd % 8 == 0 && gemm_mfma_supported(0, M, N, K, A, B, C, nullptr);
+  if (!fast) {
+    int rc = gemm(s, dtype, 0, M, N, K, A, B, C, nullptr);
+    if (rc) return rc;
+    rope(s, dtype, C, M, ra.T, ra.rot_cols / ra.hd, ra.hd, (int)N, rope_theta, +1);
+    return SP_OK;
+  }
+  const int pi = prof_start(0, s);
+  gemm_mfma(s, 0, M, N, K, A, B, C, nullptr, &ra);
+  prof_stop(pi, s, 2.0 * (double)M * (double)N * (double)K);
+  return SP_OK;
+}
+
 }  // namespace sp

@@ -50,6 +50,14 @@ void rmsnorm_bwd(hipStream_t s, int dtype, const void* dy, const void* x, const 
                  const void* dres, int64_t R, int d, void* dx, float* dg);
 // rotates the first nheads*hd columns of every row (row_stride elements apart); position = row % T
 void rope(hipStream_t s, int dtype, void* qk, int64_t R, int T, int nheads, int hd, int row_stride, float theta, int sign);
+// table[(p * hd/2 + i) * 2 + {0, 1}] = cos, sin of p * theta^(-2i/hd), the angles rope() uses, for p < T
+void rope_table(hipStream_t s, int T, int hd, float theta, float* table);
+// Rotation fused into a producer: the leading rot_cols columns of a row are heads of hd columns whose pairs
+// (2i, 2i+1) turn by the angle of position (row % T); table as written by rope_table
+struct RopeArgs {
+  const float* table;
+  int T, hd, rot_cols;
+};
 void swiglu_fwd(hipStream_t s, int dtype, const void* gu, int64_t R, int h, void* a);
 void swiglu_bwd(hipStream_t s, int dtype, const void* da, const void* gu, int64_t R, int h, void* dgu);
 // counts[mb] = number of targets >= 0 among the rows of microbatch mb
@@ -63,8 +71,14 @@ int gemm(hipStream_t s, int dtype, int op, int64_t M, int64_t N, int64_t K, cons
          const void* R);
 
 int attention_fwd(hipStream_t s, int dtype, int B, int T, int H, int Hkv, int hd, const void* qkv, void* o, float* lse);
+// rope_tab (may be null): if given, q and k in qkv are rotated vectors and dqkv is returned with respect to
+// the vectors before the rotation (theta is only used when the rotation runs as a pass of its own)
 int attention_bwd(hipStream_t s, int dtype, int B, int T, int H, int Hkv, int hd, const void* qkv, const void* o,
-                  const float* lse, const void* do_, void* dqkv, float* delta);
+                  const float* lse, const void* do_, void* dqkv, float* delta, const float* rope_tab = nullptr,
+                  float rope_theta = 0.f);
+// C = A*B^T with the rotation applied to C on the way out (same result as gemm op 0 followed by rope)
+int gemm_rope(hipStream_t s, int dtype, int64_t M, int64_t N, int64_t K, const void* A, const void* B, void* C,
+              const RopeArgs& ra, float rope_theta);
 
 // building blocks the dispatchers choose between
 void gemm_simple(hipStream_t s, int dtype, int op, int64_t M, int64_t N, int64_t K, const void* A, const void* B,
@@ -72,7 +86,7 @@ void gemm_simple(hipStream_t s, int dtype, int op, int64_t M, int64_t N, int64_t
 bool gemm_mfma_supported(int op, int64_t M, int64_t N, int64_t K, const void* A, const void* B, const void* C,
                          const void* R);
 void gemm_mfma(hipStream_t s, int op, int64_t M, int64_t N, int64_t K, const void* A, const void* B, void* C,
-               const void* R);
+               const void* R, const RopeArgs* rope = nullptr);
 void attention_simple_fwd(hipStream_t s, int dtype, int B, int T, int H, int Hkv, int hd, const void* qkv, void* o,
                           float* lse);
 void attention_simple_bwd(hipStream_t s, int dtype, int B, int T, int H, int Hkv, int hd, const void* qkv,
@@ -80,7 +94,7 @@ void attention_simple_bwd(hipStream_t s, int dtype, int B, int T, int H, int Hkv
 bool attention_flash_supported(int B, int T, int H, int Hkv, int hd);
 void attention_flash_fwd(hipStream_t s, int B, int T, int H, int Hkv, int hd, const void* qkv, void* o, float* lse);
 void attention_flash_bwd(hipStream_t s, int B, int T, int H, int Hkv, int hd, const void* qkv, const void* o,
-                         const float* lse, const void* do_, void* dqkv, float* delta);
+                         const float* lse, const void* do_, void* dqkv, float* delta, const float* rope_tab);
 
 // ---- optional per-launch timing (see sp_prof_begin); classes:
 enum { PROF_GEMM_NT = 0, PROF_GEMM_NN = 1, PROF_GEMM_TN = 2, PROF_ATTN_FWD = 3, PROF_ATTN_DELTA = 4, PROF_ATTN_DQ = 5,

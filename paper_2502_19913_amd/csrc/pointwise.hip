@@ -241,6 +241,18 @@ __global__ __launch_bounds__(kBlock) void k_rope(T* __restrict__ qk, int64_t R, 
   }
 }
 
+// cos and sin of the same angles, tabulated: entry p * hd/2 + i
+__global__ __launch_bounds__(kBlock) void k_rope_table(float2* __restrict__ table, int T_, int hd, float log2_theta) {
+  const int half = hd / 2;
+  const int idx = blockIdx.x * kBlock + threadIdx.x;
+  if (idx >= T_ * half) return;
+  const int p = idx / half, i = idx - p * half;
+  float inv = exp2f(-(float)(2 * i) / (float)hd * log2_theta);
+  float sn, cs;
+  sincosf((float)p * inv, &sn, &cs);
+  table[idx] = make_float2(cs, sn);
+}
+
 // ------------------------------------------------------------------------------------------ SwiGLU
 template <class T>
 __global__ __launch_bounds__(kBlock) void k_swiglu_fwd(const T* __restrict__ gu, int64_t R, int h, T* __restrict__ a) {
@@ -490,6 +502,12 @@ void rope(hipStream_t s, int dtype, void* qk, int64_t R, int T, int nheads, int 
     hipLaunchKernelGGL(k_rope<bf16>, dim3(grid), dim3(kBlock), 0, s, (bf16*)qk, R, T, pairs, hd, row_stride, l2, (float)sign);
   else
     hipLaunchKernelGGL(k_rope<float>, dim3(grid), dim3(kBlock), 0, s, (float*)qk, R, T, pairs, hd, row_stride, l2, (float)sign);
+}
+
+void rope_table(hipStream_t s, int T, int hd, float theta, float* table) {
+  const int n = T * (hd / 2);
+  if (n <= 0) return;
+  hipLaunchKernelGGL(k_rope_table, dim3((n + kBlock - 1) / kBlock), dim3(kBlock), 0, s, (float2*)table, T, hd, log2f(theta));
 }
 
 template <class T>
