@@ -6,7 +6,7 @@ resident in HBM: every group of the route plan through the stage forward, (for t
 workload) final norm + output head + loss, then every group through the stage backward, with the
 gradient buffer cleared at the start of the step.  Prints one JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c3|c2|c4|c5|c1]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c3|c2|c4|c5|c1] [--one-group]
 """
 import argparse
 import ctypes
@@ -156,6 +156,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--one-group", action="store_true",
+                    help="stage-share workloads: all routed microbatches as one group (upper bound of the rate)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -168,6 +170,9 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
     w = build_workload(args.config, torch, sp, synth)
+    if args.one_group and not w["whole"]:
+        mbs = sorted(m for _, _, g in w["plan"] for m in g)
+        w["plan"] = [(w["plan"][0][0], w["stage"], mbs)]
     for _ in range(args.warmup):
         step(w)
     torch.cuda.synchronize()
@@ -221,7 +226,8 @@ def main():
             "c5": "LLaMa-3-8B-shape single stage of 4 layers (GQA) + final norm + LM head + CE, 16 microbatches x 4096 "
                   "tokens under 1/3 skip with swaps",
         }[args.config], "id": args.config, "n_mb": cfg["n_mb"], "tokens_per_mb": cfg["seqs_per_mb"] * cfg["seq_len"],
-            "stage_visits": w["visits"], "groups": [len(m) for _, _, m in w["plan"]]},
+            "stage_visits": w["visits"], "groups": [len(m) for _, _, m in w["plan"]],
+            "one_group": bool(args.one_group)},
         "stage_tokens_per_s": round(w["stage_tokens"] / sec, 1),
         "tflops": round(tflops, 1),
         "frac_bf16_mfma_peak": round(tflops / PEAK_BF16_TFLOPS, 4),

@@ -63,7 +63,7 @@ __device__ __forceinline__ u32x4 make_desc(const void* p, uint32_t bytes) {
 __device__ __forceinline__ void load_to_lds16(u32x4 desc, lds_ptr lds, uint32_t voff) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds), "v"(voff), "s"(desc) : "memory");
 }
-constexpr uint32_t kPastEnd = 0x80000000u;      // operands are smaller than this (checked by the caller)
+constexpr uint32_t kPastEnd = 0x80000000u;      // no descriptor is this large
 
 // One operand's share of the tile loads for one wavefront: 4 instructions of 1 KiB per step.
 // Instruction j fills the tile's 16-byte chunks (8j + wave) * 64 + lane.
@@ -74,35 +74,43 @@ constexpr uint32_t kPastEnd = 0x80000000u;      // operands are smaller than thi
 // The permutation is applied on the memory side: a lane fetches the chunk that belongs at its position.
 template <bool KSTRIDED>
 struct Operand {
-  u32x4 desc;
-  uint32_t voff[4];    // byte offset of the lane's chunk for k0 = 0, per instruction
+  const char* base;    // first byte of the tile's rows (k-contiguous) or of its first x (k-strided), at k = 0
+  int64_t left;        // bytes from base to the end of the operand
+  uint32_t voff[4];    // byte offset of the lane's chunk from base, per instruction
   uint32_t k_step;     // byte distance of one k element
   int kc8;             // k-contiguous: first k of the lane's chunk inside a step
-  // ld: leading dimension (elements); origin: first tile row (k-contiguous) or first x (k-strided)
-  __device__ __forceinline__ void init(const bf16* X, uint32_t bytes, int ld, int origin, int wave, int lane) {
-    desc = make_desc(X, bytes);
+  // rows x ld elements in memory; origin: first tile row (k-contiguous) or first x (k-strided).
+  // Offsets stay below 2^31 for ld < 2^21 (checked by the caller); the operand itself may be larger.
+  __device__ __forceinline__ void init(const bf16* X, int64_t rows, int ld, int origin, int wave, int lane) {
+    const int64_t first = KSTRIDED ? (int64_t)origin : (int64_t)origin * ld;
+    base = reinterpret_cast<const char*>(X + first);
+    left = (rows * ld - first) * 2;
     kc8 = 0;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int q = (8 * j + wave) * 64 + lane;
       if (KSTRIDED) {
         const int krow = q >> 5, pos = q & 31, c = pos ^ ((krow & 3) << 2);
-        voff[j] = ((uint32_t)krow * ld + origin + c * 8) * 2u;
+        voff[j] = ((uint32_t)krow * ld + c * 8) * 2u;
       } else {
         const int row = q >> 3, pos = q & 7, c = pos ^ ((row >> 1) & 7);
-        voff[j] = ((uint32_t)(origin + row) * ld + c * 8) * 2u;
+        voff[j] = ((uint32_t)row * ld + c * 8) * 2u;
         kc8 = c * 8;   // the same for every j: it depends on lane and wave & 1 only
       }
     }
     k_step = KSTRIDED ? (uint32_t)ld * 2u : 2u;
   }
+  // The step's descriptor starts at the step's first k, so offsets never grow with the operand; its size
+  // is what is left of the operand, capped below kPastEnd.
   // KMASK (k-contiguous only): chunks whose k is at or past kend read as zero
   template <bool KMASK>
   __device__ __forceinline__ void load(int k0, int kend, char* tile, int wave) const {
     const bool dead = KMASK && !KSTRIDED && (k0 + kc8 >= kend);
-    const uint32_t add = (uint32_t)k0 * k_step;
+    const int64_t skip = (int64_t)k0 * k_step;
+    const int64_t rest = left - skip;
+    const u32x4 desc = make_desc(base + skip, (uint32_t)(rest < 0 ? 0 : (rest > 0x7fffffff ? 0x7fffffff : rest)));
 #pragma unroll
-    for (int j = 0; j < 4; ++j) load_to_lds16(desc, (lds_ptr)(tile + (8 * j + wave) * 1024), dead ? kPastEnd : voff[j] + add);
+    for (int j = 0; j < 4; ++j) load_to_lds16(desc, (lds_ptr)(tile + (8 * j + wave) * 1024), dead ? kPastEnd : voff[j]);
   }
 };
 
@@ -171,8 +179,8 @@ __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__
 
   Operand<AS> opa;
   Operand<BS> opb;
-  opa.init(A, (uint32_t)((size_t)M * K * 2), AS ? M : K, m0, wave, lane);
-  opb.init(B, (uint32_t)((size_t)N * K * 2), BS ? N : K, n0, wave, lane);
+  opa.init(A, AS ? K : M, AS ? M : K, m0, wave, lane);
+  opb.init(B, BS ? K : N, BS ? N : K, n0, wave, lane);
 
   // acc[j][i]: MFMA rows = 32 output columns n (i of 2), MFMA columns = 32 output rows m (j of 4)
   f32x16 acc[4][2];
@@ -320,8 +328,8 @@ int cu_count() {
 bool gemm_mfma_supported(int op, int64_t M, int64_t N, int64_t K, const void* A, const void* B, const void* C,
                          const void* R) {
   if (M < 1 || N < 1 || K < 1) return false;
-  // 31-bit byte offsets into each operand
-  if (M * K * 2 >= ((int64_t)1 << 31) || N * K * 2 >= ((int64_t)1 << 31)) return false;
+  // tile-relative byte offsets (up to 256 rows of the leading dimension) stay below 2^31
+  if (M >= (1 << 21) || N >= (1 << 21) || K >= (1 << 21)) return false;
   if (!al16(A) || !al16(B) || !al16(C) || (R && !al16(R))) return false;
   if (((M + BM - 1) / BM) * ((N + BN - 1) / BN) > (1 << 24)) return false;
   if (N % 8) return false;                      // 16-byte output chunks

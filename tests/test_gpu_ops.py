@@ -67,6 +67,31 @@ def test_gemm_long_reduction_split():
     assert relerr(c.cpu().numpy(), 2 * ref) < 1e-5
 
 
+def test_gemm_operand_larger_than_2gib():
+    # the widest activations of the 7B-shape stage: 12 microbatches x 4096 tokens x 2 x 11008 hidden is 2.16 GB.
+    # Inputs from the device's seeded generator (a host draw of a billion normals would take minutes); sampled
+    # output rows are checked against the checker's products on the matching slices.
+    R, W, N = 49152 + 8, 22016, 264
+    g = torch.Generator(device="cuda"); g.manual_seed(77)
+    big = torch.randn((R, W), generator=g, device="cuda", dtype=torch.bfloat16)
+    assert big.numel() * 2 > (1 << 31)
+    # op 1: C[R, N] = big[R, W] * B[W, N]
+    b = round_bf16(synth.normal(7, "bigb", (W, N)))
+    c = torch.empty((R, N), dtype=torch.bfloat16, device="cuda")
+    sp.gemm(1, big, dev(b, torch.bfloat16), c)
+    rows = [0, 255, 256, 30001, 48000, R - 9, R - 1]
+    ref = big[rows].float().cpu().numpy().astype(np.float64) @ b.astype(np.float64)
+    assert relerr(c[rows].float().cpu().numpy(), ref) < 4e-3
+    # op 2: C[W, N] += big[R, W]^T * D[R, N] (big is the k-strided operand)
+    d = round_bf16(synth.normal(8, "bigd", (R, N)))
+    c2 = torch.zeros((W, N), dtype=torch.float32, device="cuda")
+    sp.gemm(2, big, dev(d, torch.bfloat16), c2)
+    cols = [0, 7, 300, 11008, 22000, W - 1]
+    _, ref2 = orc.linear_bwd(big[:, cols].float().cpu().numpy().astype(np.float64), d.astype(np.float64),
+                             np.zeros((len(cols), N)))
+    assert relerr(c2[cols].cpu().numpy(), ref2) < 2e-5
+
+
 def test_gemm_rejects_bad_arguments():
     a = torch.zeros((8, 8), device="cuda")
     with pytest.raises(sp.SpError):
