@@ -105,6 +105,27 @@ def step(w):
     return None
 
 
+def optimizer_step(w, torch, sp, iters=5):
+    """The clip + AdamW update over this workload's parameters (not part of `value`): HBM-bound, 34 bytes
+    per parameter (gradient read twice, m, v and the float master read and written, bf16 copy written)."""
+    n = w["params"].numel()
+    master = w["params"].float()
+    m = torch.zeros_like(master); v = torch.zeros_like(master)
+    ws = torch.empty(sp.optim_workspace_bytes(), dtype=torch.uint8, device=master.device)
+    out = w["params"] if w["params"].dtype == torch.bfloat16 else None
+    f = lambda t: sp.optim_step(master, w["grads"], m, v, t, params_out=out, workspace=ws)
+    f(1)
+    e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for t in range(2, 2 + iters):
+        f(t)
+    e1.record(); torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / iters
+    nbytes = n * (32 + (2 if out is not None else 0))
+    return dict(ms=round(ms, 3), params=n, bytes_per_param=nbytes // n, achieved_gbs=round(nbytes / ms / 1e6, 1),
+                peak_gbs=8000.0, frac=round(nbytes / ms / 1e6 / 8000.0, 4))
+
+
 def cpu_baseline(key, synth):
     """The CPU checker timed on a bounded sample of the same workload (float32 instantiation)."""
     import numpy as np
@@ -234,6 +255,7 @@ def main():
         "roofline": roof,
         "kernels": kernels,
     }
+    out["optimizer_step"] = optimizer_step(w, torch, sp)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.config, synth)
     w["ctx"].close()

@@ -184,6 +184,26 @@ int sp_attention_fwd(void* hip_stream, int dtype, int B, int T, int H, int Hkv, 
 int sp_attention_bwd(void* hip_stream, int dtype, int B, int T, int H, int Hkv, int hd, const void* qkv,
                      const void* o, const float* lse, const void* do_, void* dqkv, float* delta_scratch);
 
+/* The update that closes an iteration (appendix "Test Configurations": learning rate 3e-4, gradient norms
+ * clipped to 1.0; the paper does not name the optimiser, this library's reading is AdamW):
+ *   g <- g * min(1, clip_norm / (||g||_2 + 1e-6))      one norm over all n gradients; clip_norm 0 = off
+ *   m <- beta1 m + (1 - beta1) g ;  v <- beta2 v + (1 - beta2) g^2
+ *   p <- p (1 - lr weight_decay) - lr (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps)
+ * master, m, v (float, n elements, updated in place) and grads (float, read only; e.g. what sp_run_paths or
+ * sp_stage_bwd accumulated) are device pointers, 16-byte aligned, owned by the caller.  params_out, if not
+ * null, receives the new parameters rounded to out_dtype (SP_BF16 or SP_F32): the copy the next iteration's
+ * kernels read.  workspace: sp_optim_workspace_bytes() bytes of device memory, 16-byte aligned, contents
+ * irrelevant before and after.  grad_norm (device, 1 float, may be null) receives the norm before clipping.
+ * step counts from 1.  Work is enqueued on hip_stream and not waited for.  The sum of squares is formed in
+ * a fixed order in double, so the result is reproducible.  SP_EINVAL: null or misaligned pointers, step < 1,
+ * hyper-parameters out of range (lr, eps, weight_decay, clip_norm < 0; beta outside [0, 1)). */
+typedef struct sp_adamw {
+  float lr, beta1, beta2, eps, weight_decay, clip_norm;
+} sp_adamw;
+int64_t sp_optim_workspace_bytes(void);
+int sp_optim_step(void* hip_stream, const sp_adamw* hyper, int64_t n, int step, float* master, const float* grads,
+                  float* m, float* v, void* params_out, int out_dtype, void* workspace, float* grad_norm);
+
 /* Measurement aid: between sp_prof_begin() and sp_prof_end() every matrix-product and attention
  * launch of this process is bracketed by HIP events on its stream.  sp_prof_end waits for them and
  * fills, per kernel class c < n_classes, the summed duration (ms), the summed algorithmic flops

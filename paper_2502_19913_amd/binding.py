@@ -22,7 +22,7 @@ SP_STRICT_CC, SP_SWAP_ANY_GAP, SP_ALLOW_ANY_ORDER = 0, 1, 2
 EXPORTS = ["sp_param_count", "sp_param_layout", "sp_workspace_bytes", "sp_make_paths", "sp_check_paths",
            "sp_route_plan", "sp_strerror", "sp_create", "sp_destroy", "sp_reset", "sp_embed_fwd", "sp_embed_bwd",
            "sp_stage_fwd", "sp_stage_bwd", "sp_head_fwd_bwd", "sp_run_paths", "sp_gemm", "sp_attention_fwd",
-           "sp_attention_bwd", "sp_prof_begin", "sp_prof_end"]
+           "sp_attention_bwd", "sp_optim_workspace_bytes", "sp_optim_step", "sp_prof_begin", "sp_prof_end"]
 
 
 class SpCfg(C.Structure):
@@ -53,6 +53,7 @@ def lib():
         _lib = C.CDLL(_LIBPATH)
         _lib.sp_strerror.restype = C.c_char_p
         _lib.sp_param_count.restype = C.c_int64
+        _lib.sp_optim_workspace_bytes.restype = C.c_int64
         _lib.sp_workspace_bytes.restype = C.c_int64
         _lib.sp_make_paths.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_uint64, C.c_void_p, C.c_void_p]
     return _lib
@@ -247,6 +248,24 @@ def attention_fwd(qkv, o, lse, B, T, H, Hkv, hd, stream=None):
 def attention_bwd(qkv, o, lse, do, dqkv, delta, B, T, H, Hkv, hd, stream=None):
     _check(lib().sp_attention_bwd(_stream_ptr(stream), C.c_int(_dt(qkv)), B, T, H, Hkv, hd, _dptr(qkv), _dptr(o),
                                   _dptr(lse), _dptr(do), _dptr(dqkv), _dptr(delta)))
+
+
+class SpAdamW(C.Structure):
+    _fields_ = [(n, C.c_float) for n in ("lr", "beta1", "beta2", "eps", "weight_decay", "clip_norm")]
+
+
+def optim_workspace_bytes() -> int:
+    return int(lib().sp_optim_workspace_bytes())
+
+
+def optim_step(master, grads, m, v, step: int, params_out=None, workspace=None, grad_norm=None, lr=3e-4, beta1=0.9,
+               beta2=0.999, eps=1e-8, weight_decay=0.01, clip_norm=1.0, stream=None):
+    """Clip + AdamW update of the float master copy (in place); params_out receives its low-precision copy."""
+    h = SpAdamW(lr, beta1, beta2, eps, weight_decay, clip_norm)
+    n = master.numel()
+    od = _dt(params_out) if params_out is not None else SP_F32
+    _check(lib().sp_optim_step(_stream_ptr(stream), C.byref(h), C.c_int64(n), C.c_int(step), _dptr(master), _dptr(grads),
+                               _dptr(m), _dptr(v), _dptr(params_out), C.c_int(od), _dptr(workspace), _dptr(grad_norm)))
 
 
 PROF_CLASSES = ["gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd", "attn_delta", "attn_dq", "attn_dkv", "gemm_plain",

@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libskippipe.so")
 SOURCES = ["host.cpp", "engine.hip", "pointwise.hip", "gemm_simple.hip", "gemm_mfma.hip", "attn_simple.hip",
-           "attn_flash.hip", "prof.hip"]
+           "attn_flash.hip", "prof.hip", "optim.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

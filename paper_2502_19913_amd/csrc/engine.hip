@@ -202,7 +202,7 @@ int sp_create(const sp_cfg* cfg, void* hip_stream, int n_mb_max, int n_visits_ma
   rope_table(c->stream, (int)Dims(*cfg).T, (int)Dims(*cfg).hd, cfg->rope_theta, c->rope_tab);
   e = hipGetLastError();
   if (e != hipSuccess) {
-    hipFree(c->base);
+    (void)hipFree(c->base);
     delete c;
     return hip_fail((int)e, "rope table");
   }
