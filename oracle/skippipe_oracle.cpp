@@ -476,6 +476,47 @@ int run_paths(const Cfg& c, const F* P, const int32_t* tokens, const F* x_in, co
   return 0;
 }
 
+// ---------------------------------------------------------------- evaluation under stage drops, forward only
+// Section "Fault Tolerant Inference": every sample runs the stages of its path (stage 0 is never dropped);
+// where the number of stages to drop is not whole, one stage of the path runs only the first half of its
+// layers.  half[mb] names that stage (-1: none); "the first half" of an odd count is read as the first
+// floor(layers_per_stage / 2) layers.  Returns each microbatch's mean loss; perplexity is its exponential.
+template <class F>
+int eval_paths(const Cfg& c, const F* P, const int32_t* tokens, const int32_t* targets, const int32_t* paths,
+               const int32_t* len, const int32_t* half, int n_mb, F* loss_mb, F* loss_total) {
+  if (!c.has_embed || !c.has_head || c.local_stage_begin != 0 || c.local_stage_count != c.n_stages) return -3;
+  const Layout L = make_layout(c);
+  const int d = c.dim, B = c.seqs_per_mb, T = c.seq_len, R = B * T, V = c.vocab;
+  const size_t n = (size_t)R * d;
+  F total = 0;
+  for (int mb = 0; mb < n_mb; ++mb) {
+    const int32_t* p = paths + (size_t)mb * c.n_stages;
+    Vec<F> x(n), y(n);
+    for (int r = 0; r < R; ++r) {
+      int tk = tokens[(size_t)mb * R + r];
+      if (tk < 0 || tk >= V) return -1;
+      for (int k = 0; k < d; ++k) x[(size_t)r * d + k] = P[L.embed + (size_t)tk * d + k];
+    }
+    for (int j = 0; j < len[mb]; ++j) {
+      const int st = p[j];
+      if (st < 0 || st >= c.n_stages) return -2;
+      const int n_layers = (half && half[mb] == st) ? c.layers_per_stage / 2 : c.layers_per_stage;
+      for (int l = 0; l < n_layers; ++l) {
+        BlockCache<F> scratch;
+        block_fwd<F>(c, P, L.layers[(size_t)st * c.layers_per_stage + l], x.data(), B, y.data(), scratch);
+        x.swap(y);
+      }
+    }
+    Vec<F> xn(n), rstd(R), logits((size_t)R * V), dlogits((size_t)R * V);
+    rmsnorm_fwd<F>(x.data(), P + L.gf, R, d, F(c.rms_eps), xn.data(), rstd.data());
+    linear_fwd<F>(xn.data(), P + L.whead, R, d, V, logits.data());
+    loss_mb[mb] = cross_entropy<F>(logits.data(), targets + (size_t)mb * R, R, V, F(1), dlogits.data());
+    total += loss_mb[mb];
+  }
+  if (loss_total) *loss_total = total / F(n_mb);
+  return 0;
+}
+
 }  // namespace
 
 // ---------------------------------------------------------------- C entry points (ctypes)
@@ -487,6 +528,11 @@ int run_paths(const Cfg& c, const F* P, const int32_t* tokens, const F* x_in, co
                                     F* G) {                                                                         \
     return run_paths<F>(*c, P, tokens, x_in, targets, dy_in, paths, len, n_mb, loss_mb, loss_total, y_out, dx_out,  \
                         G);                                                                                         \
+  }                                                                                                                 \
+  extern "C" int orc_eval_paths##SUF(const Cfg* c, const F* P, const int32_t* tokens, const int32_t* targets,       \
+                                     const int32_t* paths, const int32_t* len, const int32_t* half, int n_mb,       \
+                                     F* loss_mb, F* loss_total) {                                                   \
+    return eval_paths<F>(*c, P, tokens, targets, paths, len, half, n_mb, loss_mb, loss_total);                      \
   }                                                                                                                 \
   extern "C" void orc_rmsnorm_fwd##SUF(const F* x, const F* g, int R, int d, F eps, F* y, F* rstd) {                \
     rmsnorm_fwd<F>(x, g, R, d, eps, y, rstd);                                                                       \

@@ -162,6 +162,29 @@ def rmsnorm_bwd(dy, x, g, rstd):
     return dx, dg
 
 
+def eval_paths(cfg: dict, named_params: Dict[str, np.ndarray], paths: np.ndarray, lens: np.ndarray, *,
+               tokens: np.ndarray, targets: np.ndarray, half: Optional[np.ndarray] = None, dtype=np.float64) -> dict:
+    """Forward only: every microbatch along its path, the stage half[mb] (if >= 0) with only the first half
+    of its layers; returns ``loss`` (mean over microbatches) and ``loss_mb``."""
+    suf, ft = _suf(dtype)
+    n_mb = int(paths.shape[0])
+    R = cfg["seqs_per_mb"] * cfg["seq_len"]
+    P = pack(cfg, named_params, dtype)
+    paths = np.ascontiguousarray(paths, np.int32)
+    assert paths.shape == (n_mb, cfg["n_stages"])
+    lens = np.ascontiguousarray(lens, np.int32)
+    tok = np.ascontiguousarray(tokens, np.int32).reshape(n_mb, R)
+    tgt = np.ascontiguousarray(targets, np.int32).reshape(n_mb, R)
+    hf = None if half is None else np.ascontiguousarray(half, np.int32).reshape(n_mb)
+    loss_mb = np.zeros(n_mb, dtype)
+    loss = np.zeros(1, dtype)
+    rc = getattr(lib(), "orc_eval_paths" + suf)(C.byref(_cfg(cfg)), _p(P), _p(tok), _p(tgt), _p(paths), _p(lens),
+                                                _p(hf), C.c_int(n_mb), _p(loss_mb), _p(loss))
+    if rc != 0:
+        raise ValueError(f"oracle rejected its input (code {rc})")
+    return dict(loss=float(loss[0]), loss_mb=loss_mb)
+
+
 def linear_fwd(x, W):
     suf, ft = _suf(x.dtype)
     R, K = x.shape; N = W.shape[0]

@@ -76,3 +76,21 @@ def run(cfg, named, paths, lens, tokens=None, targets=None, x_in=None, dy_in=Non
                 loss_mb=[float(l.detach()) for l in loss_mb], grads=grads,
                 y=torch.stack([y.detach() for y in ys]).numpy(),
                 dx=None if cfg["has_embed"] else torch.stack([x.grad for x in xs]).numpy())
+
+
+def eval_losses(cfg, named, paths, lens, tokens, targets, half=None, dtype=torch.float64):
+    """Forward only: per-microbatch loss of the ordinary model built from the layers of the stages on the
+    path, the stage half[mb] contributing only its first layers_per_stage // 2 layers."""
+    p = {k: torch.tensor(v, dtype=dtype) for k, v in named.items()}
+    B, T, d, Lps = cfg["seqs_per_mb"], cfg["seq_len"], cfg["dim"], cfg["layers_per_stage"]
+    out = []
+    for mb in range(paths.shape[0]):
+        x = Fn.embedding(torch.tensor(tokens[mb].reshape(-1), dtype=torch.long), p["embed"])
+        for s in paths[mb, :lens[mb]]:
+            n = Lps // 2 if half is not None and half[mb] == s else Lps
+            for l in range(n):
+                x = layer(cfg, p, f"s{s}.l{l}.", x, B)
+        xn = Fn.rms_norm(x, (d,), p["gf"], cfg["rms_eps"])
+        out.append(float(Fn.cross_entropy(xn @ p["whead"].T, torch.tensor(targets[mb].reshape(-1), dtype=torch.long),
+                                          ignore_index=-1)))
+    return out
