@@ -126,6 +126,41 @@ def optimizer_step(w, torch, sp, iters=5):
                 peak_gbs=8000.0, frac=round(nbytes / ms / 1e6 / 8000.0, 4))
 
 
+def eval_mode(args, w, torch, sp, synth):
+    """Forward-only evaluation under stage drops (the fault-tolerant inference setting): one JSON line."""
+    cfg = w["cfg"]
+    if not w["whole"]:
+        print("--eval-skip needs a whole-model workload (c1 or c2)", file=sys.stderr)
+        sys.exit(2)
+    num, den = (int(x) for x in args.eval_skip.split("/"))
+    paths, lens, half = synth.make_eval_paths(cfg["n_stages"], cfg["n_mb"], num, den, synth.BASE_SEED)
+    ctx, Nmb = w["ctx"], cfg["seqs_per_mb"] * cfg["seq_len"]
+    run = lambda: ctx.eval_paths(w["params"], w["tok"], w["tgt"], paths, lens, half)
+    for _ in range(args.warmup):
+        run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        loss, _ = run()
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / args.steps
+    Lps = cfg["layers_per_stage"]
+    layers = sum(int(lens[mb]) * Lps - (Lps - Lps // 2 if half[mb] >= 0 else 0) for mb in range(cfg["n_mb"]))
+    fl = flops_per_token_layer(cfg) * layers * Nmb + 2.0 * cfg["dim"] * cfg["vocab"] * cfg["n_mb"] * Nmb
+    out = {"metric": "forward-only evaluation tokens/sec under per-sample stage drops on 1 MI355X",
+           "value": round(cfg["n_mb"] * Nmb / sec, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": round(sec * 1e3, 3), "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "bf16" if cfg["dtype"] == "bf16" else "f32",
+           "data": "synthetic (seeded): N(0,0.02) weights, uniform tokens, seeded drops",
+           "config": {"workload": f"{args.config} whole model, forward only, {args.eval_skip} of the stages dropped per "
+                                  f"sample", "id": args.config, "n_mb": cfg["n_mb"], "tokens_per_mb": Nmb,
+                      "layers_run": layers, "half_stages": int((half >= 0).sum())},
+           "tflops": round(fl / sec / 1e12, 1), "frac_bf16_mfma_peak": round(fl / sec / 1e12 / PEAK_BF16_TFLOPS, 4),
+           "loss": round(loss, 4)}
+    ctx.close()
+    print(json.dumps(out))
+
+
 def cpu_baseline(key, synth):
     """The CPU checker timed on a bounded sample of the same workload (float32 instantiation)."""
     import numpy as np
@@ -177,6 +212,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--eval-skip", default=None, metavar="NUM/DEN",
+                    help="whole-model workloads (c1, c2): time forward-only evaluation with this share of the "
+                         "stages dropped per sample (a half stage where the count ends in .5) instead of training")
     ap.add_argument("--one-group", action="store_true",
                     help="stage-share workloads: all routed microbatches as one group (upper bound of the rate)")
     args = ap.parse_args()
@@ -191,6 +229,8 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
     w = build_workload(args.config, torch, sp, synth)
+    if args.eval_skip:
+        return eval_mode(args, w, torch, sp, synth)
     if args.one_group and not w["whole"]:
         mbs = sorted(m for _, _, g in w["plan"] for m in g)
         w["plan"] = [(w["plan"][0][0], w["stage"], mbs)]

@@ -184,6 +184,19 @@ int sp_attention_fwd(void* hip_stream, int dtype, int B, int T, int H, int Hkv, 
 int sp_attention_bwd(void* hip_stream, int dtype, int B, int T, int H, int Hkv, int hd, const void* qkv,
                      const void* o, const float* lse, const void* do_, void* dqkv, float* delta_scratch);
 
+/* Forward-only evaluation under stage drops (section "Fault Tolerant Inference"): every microbatch (sample)
+ * runs the stages of its path, stage 0 always among them; the number of stages may differ between samples.
+ * half_stage (host, int32[n_mb], may be null; entries -1 = none): the one stage of a sample's path that
+ * executes only the first layers_per_stage / 2 of its layers (the paper's partial stage skip for skip ratios
+ * that do not divide the stage count; "the first half" of an odd count is read as rounded down).  It must be
+ * on the path, must not be stage 0, and needs layers_per_stage >= 2 (SP_EPATH otherwise).  Paths are checked
+ * as in sp_check_paths except for equal lengths.  Needs the whole model on this node.  Nothing is kept for a
+ * backward pass.  loss_host (host, 1 float): mean over microbatches of the mean loss over non-ignored
+ * targets; loss_mb_host (host, n_mb floats, may be null): each microbatch's own; perplexity is exp(loss).
+ * Waits for the stream. */
+int sp_eval_paths(sp_ctx* ctx, const void* params, const int32_t* tokens, const int32_t* targets, const int32_t* paths,
+                  const int32_t* len, const int32_t* half_stage, int n_mb, float* loss_host, float* loss_mb_host);
+
 /* The update that closes an iteration (appendix "Test Configurations": learning rate 3e-4, gradient norms
  * clipped to 1.0; the paper does not name the optimiser, this library's reading is AdamW):
  *   g <- g * min(1, clip_norm / (||g||_2 + 1e-6))      one norm over all n gradients; clip_norm 0 = off

@@ -21,7 +21,7 @@ SP_STRICT_CC, SP_SWAP_ANY_GAP, SP_ALLOW_ANY_ORDER = 0, 1, 2
 
 EXPORTS = ["sp_param_count", "sp_param_layout", "sp_workspace_bytes", "sp_make_paths", "sp_check_paths",
            "sp_route_plan", "sp_strerror", "sp_create", "sp_destroy", "sp_reset", "sp_embed_fwd", "sp_embed_bwd",
-           "sp_stage_fwd", "sp_stage_bwd", "sp_head_fwd_bwd", "sp_run_paths", "sp_gemm", "sp_attention_fwd",
+           "sp_stage_fwd", "sp_stage_bwd", "sp_head_fwd_bwd", "sp_run_paths", "sp_eval_paths", "sp_gemm", "sp_attention_fwd",
            "sp_attention_bwd", "sp_optim_workspace_bytes", "sp_optim_step", "sp_prof_begin", "sp_prof_end"]
 
 
@@ -214,6 +214,17 @@ class Context:
         loss_mb = np.zeros(n_mb, np.float32)
         _check(lib().sp_run_paths(self._h, _dptr(params), _dptr(tokens), _dptr(targets), _iptr(paths), _iptr(lens),
                                   C.c_int(n_mb), _iptr(loss), _iptr(loss_mb), _dptr(grads)))
+        return float(loss[0]), loss_mb
+
+    def eval_paths(self, params, tokens, targets, paths: np.ndarray, lens: np.ndarray, half=None):
+        paths = np.ascontiguousarray(paths, np.int32)
+        lens = np.ascontiguousarray(lens, np.int32)
+        n_mb = len(lens)
+        hf = None if half is None else np.ascontiguousarray(half, np.int32)
+        loss = np.zeros(1, np.float32)
+        loss_mb = np.zeros(n_mb, np.float32)
+        _check(lib().sp_eval_paths(self._h, _dptr(params), _dptr(tokens), _dptr(targets), _iptr(paths), _iptr(lens),
+                                   _iptr(hf) if hf is not None else None, C.c_int(n_mb), _iptr(loss), _iptr(loss_mb)))
         return float(loss[0]), loss_mb
 
 

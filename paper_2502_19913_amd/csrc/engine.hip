@@ -247,7 +247,12 @@ int sp_embed_bwd(sp_ctx* ctx, const int32_t* tokens, const void* dact_pool, int 
   return SP_OK;
 }
 
-int sp_stage_fwd(sp_ctx* ctx, int stage, const void* params, void* act_pool, const int32_t* mb_idx, int n_group) {
+}  // extern "C"
+
+// The stage's first n_layers layers on a group of slots.  keep: the visit stays on record for its backward;
+// otherwise its saved tensors are released at once (forward-only evaluation).
+static int stage_fwd_impl(sp_ctx* ctx, int stage, const void* params, void* act_pool, const int32_t* mb_idx, int n_group,
+                          int n_layers, bool keep) {
   if (!ctx || !params || !act_pool) return fail(SP_EINVAL, "stage_fwd: null argument");
   SlotList sl{};
   int rc = check_group(ctx, stage, mb_idx, n_group, &sl);
@@ -263,7 +268,7 @@ int sp_stage_fwd(sp_ctx* ctx, int stage, const void* params, void* act_pool, con
   rec.mb.assign(mb_idx, mb_idx + n_group);
   rec.arena_begin = ctx->arena_top;
   rec.live = true;
-  rec.layers.resize(cfg.layers_per_stage);
+  rec.layers.resize(n_layers);
   for (auto& ls : rec.layers) {
     char* p;
 #define SP_TAKE(field, bytes)                                   \
@@ -281,10 +286,10 @@ int sp_stage_fwd(sp_ctx* ctx, int stage, const void* params, void* act_pool, con
   gather_slots(s, dt, act_pool, sl, D.Nmb, (int)D.d, rec.layers[0].x);
   const int loc = stage - cfg.local_stage_begin;
   const int Bg = (int)(n_group * D.B);
-  for (int l = 0; l < cfg.layers_per_stage; ++l) {
+  for (int l = 0; l < n_layers; ++l) {
     const LayerOff& w = ctx->L.layers[(size_t)loc * cfg.layers_per_stage + l];
     LayerSaved& ls = rec.layers[l];
-    char* y = l + 1 < cfg.layers_per_stage ? rec.layers[l + 1].x : at(ctx, ctx->w.t_y);
+    char* y = l + 1 < n_layers ? rec.layers[l + 1].x : at(ctx, ctx->w.t_y);
     rmsnorm_fwd(s, dt, ls.x, P(ctx, params, w.g1), R, (int)D.d, cfg.rms_eps, ls.xn, ls.rstd1);
     // q, k, v = xn Wqkv^T, the heads of q and k rotated by their positions
     const RopeArgs ra = {ctx->rope_tab, (int)D.T, (int)D.hd, (int)((D.H + D.Hkv) * D.hd)};
@@ -298,8 +303,16 @@ int sp_stage_fwd(sp_ctx* ctx, int stage, const void* params, void* act_pool, con
   }
   scatter_slots(s, dt, at(ctx, ctx->w.t_y), sl, D.Nmb, (int)D.d, act_pool);
   SP_HIP(hipGetLastError());
-  ctx->records.push_back(std::move(rec));
+  if (keep) ctx->records.push_back(std::move(rec));
+  else ctx->arena_top = rec.arena_begin;   // stream order: the next visit's kernels run after this one's
   return SP_OK;
+}
+
+extern "C" {
+
+int sp_stage_fwd(sp_ctx* ctx, int stage, const void* params, void* act_pool, const int32_t* mb_idx, int n_group) {
+  if (!ctx) return fail(SP_EINVAL, "stage_fwd: null argument");
+  return stage_fwd_impl(ctx, stage, params, act_pool, mb_idx, n_group, ctx->cfg.layers_per_stage, true);
 }
 
 int sp_stage_bwd(sp_ctx* ctx, int stage, const void* params, void* dact_pool, const int32_t* mb_idx, int n_group,
@@ -363,9 +376,12 @@ int sp_stage_bwd(sp_ctx* ctx, int stage, const void* params, void* dact_pool, co
   return SP_OK;
 }
 
-int sp_head_fwd_bwd(sp_ctx* ctx, const void* params, const void* act_pool, const int32_t* targets, int n_mb,
-                    float* loss_mb, void* dact_pool, float* grads) {
-  if (!ctx || !params || !act_pool || !targets || !loss_mb || !dact_pool || !grads)
+}  // extern "C"
+
+// final norm, output head, loss; backward: also the gradients (dact_pool, grads), else the loss only
+static int head_impl(sp_ctx* ctx, const void* params, const void* act_pool, const int32_t* targets, int n_mb,
+                     float* loss_mb, void* dact_pool, float* grads, bool backward) {
+  if (!ctx || !params || !act_pool || !targets || !loss_mb || (backward && (!dact_pool || !grads)))
     return fail(SP_EINVAL, "head: null argument");
   const sp_cfg& cfg = ctx->cfg;
   if (!cfg.has_head) return fail(SP_EINVAL, "this node holds no output head");
@@ -386,15 +402,75 @@ int sp_head_fwd_bwd(sp_ctx* ctx, const void* params, const void* act_pool, const
   for (int64_t r0 = 0; r0 < Rtot; r0 += CH) {
     const int64_t R = std::min(CH, Rtot - r0);
     const char* x = (const char*)act_pool + r0 * D.d * D.E;
-    char* dx = (char*)dact_pool + r0 * D.d * D.E;
+    char* dx = backward ? (char*)dact_pool + r0 * D.d * D.E : nullptr;
     rmsnorm_fwd(s, dt, x, P(ctx, params, ctx->L.gf), R, (int)D.d, cfg.rms_eps, xn, rstd);
     if ((rc = gemm(s, dt, 0, R, D.V, D.d, xn, P(ctx, params, ctx->L.whead), logits, nullptr))) return rc;
     cross_entropy(s, dt, logits, targets, r0, R, (int)D.V, D.Nmb, counts, 1.0f / (float)n_mb, loss_mb);
+    if (!backward) continue;
     if ((rc = gemm(s, dt, 2, D.V, D.d, R, logits, xn, grads + ctx->L.whead, nullptr))) return rc;
     if ((rc = gemm(s, dt, 1, R, D.d, D.V, logits, P(ctx, params, ctx->L.whead), dxn, nullptr))) return rc;
     rmsnorm_bwd(s, dt, dxn, x, P(ctx, params, ctx->L.gf), rstd, nullptr, R, (int)D.d, dx, grads + ctx->L.gf);
   }
   SP_HIP(hipGetLastError());
+  return SP_OK;
+}
+
+extern "C" {
+
+int sp_head_fwd_bwd(sp_ctx* ctx, const void* params, const void* act_pool, const int32_t* targets, int n_mb,
+                    float* loss_mb, void* dact_pool, float* grads) {
+  return head_impl(ctx, params, act_pool, targets, n_mb, loss_mb, dact_pool, grads, true);
+}
+
+int sp_eval_paths(sp_ctx* ctx, const void* params, const int32_t* tokens, const int32_t* targets, const int32_t* paths,
+                  const int32_t* len, const int32_t* half_stage, int n_mb, float* loss_host, float* loss_mb_host) {
+  if (!ctx || !params || !tokens || !targets || !paths || !len || !loss_host)
+    return fail(SP_EINVAL, "eval_paths: null argument");
+  const sp_cfg& cfg = ctx->cfg;
+  if (!cfg.has_embed || !cfg.has_head || cfg.local_stage_begin != 0 || cfg.local_stage_count != cfg.n_stages)
+    return fail(SP_EINVAL, "eval_paths needs the whole model on this node (all stages, embedding, head)");
+  if (n_mb < 1 || n_mb > ctx->n_mb_max) return fail(SP_EINVAL, "eval_paths: n_mb outside [1, n_mb_max]");
+  const int s_n = cfg.n_stages, half_layers = cfg.layers_per_stage / 2;
+  int rc, lmax = 0;
+  for (int mb = 0; mb < n_mb; ++mb) {
+    const int32_t* p = paths + (size_t)mb * s_n;
+    if ((rc = check_one_path(cfg, p, len[mb], mb))) return rc;   // samples may drop different numbers of stages
+    lmax = std::max(lmax, (int)len[mb]);
+    if (half_stage && half_stage[mb] >= 0) {
+      const int h = half_stage[mb];
+      if (h == 0 || half_layers < 1 || std::find(p, p + len[mb], h) == p + len[mb])
+        return fail(SP_EPATH, "half_stage of microbatch " + std::to_string(mb) +
+                                  ": must be a stage of the path other than stage 0, with at least 2 layers per stage");
+    }
+  }
+  sp_reset(ctx);
+  hipStream_t s = ctx->stream;
+  char* pool_a = at(ctx, ctx->w.pool_a);
+  float* loss_mb = (float*)at(ctx, ctx->w.loss_mb);
+  if ((rc = sp_embed_fwd(ctx, params, tokens, n_mb, pool_a))) return rc;
+  // route plan: at each path position, one group per (stage, whole or half)
+  std::vector<int32_t> g;
+  for (int pos = 0; pos < lmax; ++pos)
+    for (int st = 0; st < s_n; ++st)
+      for (int half = 0; half < 2; ++half) {
+        g.clear();
+        for (int mb = 0; mb < n_mb; ++mb)
+          if (pos < len[mb] && paths[(size_t)mb * s_n + pos] == st &&
+              (half == 1) == (half_stage != nullptr && half_stage[mb] == st))
+            g.push_back(mb);
+        if (g.empty()) continue;
+        if ((rc = stage_fwd_impl(ctx, st, params, pool_a, g.data(), (int)g.size(),
+                                 half ? half_layers : cfg.layers_per_stage, false)))
+          return rc;
+      }
+  if ((rc = head_impl(ctx, params, pool_a, targets, n_mb, loss_mb, nullptr, nullptr, false))) return rc;
+  ctx->host_loss.resize(n_mb);
+  SP_HIP(hipMemcpyAsync(ctx->host_loss.data(), loss_mb, n_mb * sizeof(float), hipMemcpyDeviceToHost, s));
+  SP_HIP(hipStreamSynchronize(s));
+  double tot = 0;
+  for (int i = 0; i < n_mb; ++i) tot += ctx->host_loss[i];
+  *loss_host = (float)(tot / n_mb);
+  if (loss_mb_host) std::memcpy(loss_mb_host, ctx->host_loss.data(), n_mb * sizeof(float));
   return SP_OK;
 }
 

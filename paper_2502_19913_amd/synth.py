@@ -219,6 +219,34 @@ def make_paths(n_stages: int, n_mb: int, skip_num: int, skip_den: int, allow_swa
     return paths, lens
 
 
+def make_eval_paths(n_stages: int, n_mb: int, skip_num: int, skip_den: int,
+                    seed: int = BASE_SEED) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Per-sample paths for evaluation under stage drops: ``(paths, lens, half)``.
+
+    Every sample drops ``n_stages * skip_num / skip_den`` stages chosen at random among stages ``1..s-1``
+    (its own seeded draw); when that number ends in a half, one more stage of the sample runs only the first
+    half of its layers and is named in ``half[mb]`` (else -1).  Kept stages stay in model order.
+    """
+    s = n_stages
+    twice = (2 * s * skip_num) // skip_den                   # number of half stages to drop
+    whole, part = twice // 2, twice % 2
+    if whole + part > s - 1:
+        raise ValueError("skip ratio leaves no room for stage 0")
+    r = raw_u64(seed, "eval_paths", n_mb * max(1, s - 1))
+    paths = np.full((n_mb, s), -1, dtype=np.int32)
+    lens = np.zeros(n_mb, dtype=np.int32)
+    half = np.full(n_mb, -1, dtype=np.int32)
+    for mb in range(n_mb):
+        order = 1 + np.argsort(r[mb * (s - 1):(mb + 1) * (s - 1)], kind="stable") if s > 1 else np.zeros(0, np.int64)
+        dropped = set(int(x) for x in order[:whole])
+        if part:
+            half[mb] = int(order[whole])
+        kept = [st for st in range(s) if st not in dropped]
+        paths[mb, :len(kept)] = kept
+        lens[mb] = len(kept)
+    return paths, lens, half
+
+
 # The eight microbatches a stage-3 node of the 6-stage, 1/3-skip set-up serves in one wave: each path keeps 4
 # of 6 stages and holds stage 3, which they reach at path position 1, 2 or 3 (groups of 3, 3 and 2), three of
 # them through an exchanged pair of neighbouring stages.

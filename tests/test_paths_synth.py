@@ -73,3 +73,20 @@ def test_validator_rejects_violations():
     pathcheck.check_one([0, 1, 3, 2], 4)             # the paper's swap example
     with pytest.raises(AssertionError):
         pathcheck.check_one([0, 2, 3, 1], 4, strict=False)   # a rotation, not one adjacent exchange
+
+
+def test_eval_paths_drop_counts_and_half_stage():
+    # 6 stages: 25 % = 1.5 stages (one dropped, one half), 1/3 = 2, 50 % = 3; stage 0 is never touched
+    for (num, den), (whole, part) in {(1, 4): (1, 1), (1, 3): (2, 0), (1, 2): (3, 0), (0, 1): (0, 0)}.items():
+        paths, lens, half = synth.make_eval_paths(6, 32, num, den, 11)
+        assert (lens == 6 - whole).all() and (paths[:, 0] == 0).all()
+        for mb in range(32):
+            kept = list(paths[mb, :lens[mb]])
+            assert kept == sorted(kept) and len(set(kept)) == len(kept) and (paths[mb, lens[mb]:] == -1).all()
+            assert (half[mb] >= 1 and half[mb] in kept) if part else half[mb] == -1
+        # drops differ between samples (a per-sample draw) and depend on the seed alone
+        assert len({tuple(p) for p in paths}) > 1 or whole == 0
+        again = synth.make_eval_paths(6, 32, num, den, 11)
+        assert all((a == b).all() for a, b in zip((paths, lens, half), again))
+    with pytest.raises(ValueError):
+        synth.make_eval_paths(2, 4, 3, 4, 1)
