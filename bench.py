@@ -215,6 +215,9 @@ def main():
     ap.add_argument("--eval-skip", default=None, metavar="NUM/DEN",
                     help="whole-model workloads (c1, c2): time forward-only evaluation with this share of the "
                          "stages dropped per sample (a half stage where the count ends in .5) instead of training")
+    ap.add_argument("--serial", action="store_true",
+                    help="keep the weight-gradient products in line on the one stream (no side stream) for the "
+                         "whole run; by default only the per-launch timing pass runs that way")
     ap.add_argument("--one-group", action="store_true",
                     help="stage-share workloads: all routed microbatches as one group (upper bound of the rate)")
     args = ap.parse_args()
@@ -234,6 +237,7 @@ def main():
     if args.one_group and not w["whole"]:
         mbs = sorted(m for _, _, g in w["plan"] for m in g)
         w["plan"] = [(w["plan"][0][0], w["stage"], mbs)]
+    w["ctx"].set_side_stream(not args.serial)
     for _ in range(args.warmup):
         step(w)
     torch.cuda.synchronize()
@@ -244,11 +248,16 @@ def main():
     t1 = time.perf_counter()
     sec = (t1 - t0) / args.steps
 
-    # second pass of the same steps with HIP events around every matrix-product and attention launch
+    # second pass of the same steps with HIP events around every matrix-product and attention launch, all on
+    # the one stream: a launch's duration is then its own, not that of two kernels sharing the GPU
+    w["ctx"].set_side_stream(False)
     sp.prof_begin()
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
     for _ in range(args.steps):
         step(w)
     torch.cuda.synchronize()
+    sec_serial = (time.perf_counter() - t2) / args.steps
     prof = sp.prof_end()
     gemm_cls = [k for k in ("gemm_nt", "gemm_nn", "gemm_tn") if prof[k]["launches"]]
     roof = None
@@ -275,6 +284,7 @@ def main():
         "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(sec * 1e3, 3),
+        "ms_per_step_one_stream_timed_launches": round(sec_serial * 1e3, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg["dtype"] == "bf16" else "f32",
         "data": "synthetic (seeded): N(0,0.02) weights, N(0,1) activations or uniform tokens, seeded paths",

@@ -132,6 +132,13 @@ const char* sp_strerror(int status);
 int sp_create(const sp_cfg* cfg, void* hip_stream, int n_mb_max, int n_visits_max, sp_ctx** out);
 int sp_destroy(sp_ctx* ctx);
 
+/* sp_stage_bwd (and sp_run_paths through it) runs the four weight-gradient products of a layer on a second
+ * stream owned by the context, beside the chain that carries the activation gradient down the layers, and
+ * joins that stream back into the caller's before it returns: for the caller all work is still ordered on
+ * its own stream.  enabled = 0 keeps everything in line on the caller's stream (the per-launch timings of
+ * sp_prof_begin/end are then not inflated by kernels that share the GPU); the default is 1. */
+int sp_set_side_stream(sp_ctx* ctx, int enabled);
+
 /* Forgets every saved forward (e.g. after an aborted iteration). */
 int sp_reset(sp_ctx* ctx);
 

@@ -20,7 +20,7 @@ SP_F32, SP_BF16 = 0, 1
 SP_STRICT_CC, SP_SWAP_ANY_GAP, SP_ALLOW_ANY_ORDER = 0, 1, 2
 
 EXPORTS = ["sp_param_count", "sp_param_layout", "sp_workspace_bytes", "sp_make_paths", "sp_check_paths",
-           "sp_route_plan", "sp_strerror", "sp_create", "sp_destroy", "sp_reset", "sp_embed_fwd", "sp_embed_bwd",
+           "sp_route_plan", "sp_strerror", "sp_create", "sp_destroy", "sp_reset", "sp_set_side_stream", "sp_embed_fwd", "sp_embed_bwd",
            "sp_stage_fwd", "sp_stage_bwd", "sp_head_fwd_bwd", "sp_run_paths", "sp_eval_paths", "sp_gemm", "sp_attention_fwd",
            "sp_attention_bwd", "sp_optim_workspace_bytes", "sp_optim_step", "sp_prof_begin", "sp_prof_end"]
 
@@ -215,6 +215,9 @@ class Context:
         _check(lib().sp_run_paths(self._h, _dptr(params), _dptr(tokens), _dptr(targets), _iptr(paths), _iptr(lens),
                                   C.c_int(n_mb), _iptr(loss), _iptr(loss_mb), _dptr(grads)))
         return float(loss[0]), loss_mb
+
+    def set_side_stream(self, enabled: bool):
+        _check(lib().sp_set_side_stream(self._h, C.c_int(1 if enabled else 0)))
 
     def eval_paths(self, params, tokens, targets, paths: np.ndarray, lens: np.ndarray, half=None):
         paths = np.ascontiguousarray(paths, np.int32)

@@ -70,7 +70,7 @@ int64_t head_chunk_rows(const Dims& D, int64_t total_rows) {
 }
 
 struct Carve {
-  size_t arena, t_y, t_d0, t_d1, t_d2, t_da, t_dgu, t_dqkv, t_delta, rope, h_xn, h_rstd, h_logits, h_dxn, pool_a, pool_d,
+  size_t arena, t_y, t_dy[2], t_dh[2], t_d2, t_da, t_dgu[2], t_dqkv[2], t_delta, rope, h_xn, h_rstd, h_logits, h_dxn, pool_a, pool_d,
       loss_mb, counts, total;
   size_t arena_bytes;
 };
@@ -84,12 +84,16 @@ Carve carve(const sp_cfg& c, int n_mb_max, int n_visits_max) {
   w.arena_bytes = (size_t)n_visits_max * c.layers_per_stage * layer_saved_bytes(D, D.Nmb);
   w.arena = take(w.arena_bytes);
   w.t_y = take(Rmax * D.d * D.E);
-  w.t_d0 = take(Rmax * D.d * D.E);
-  w.t_d1 = take(Rmax * D.d * D.E);
+  // two sets of the gradients a weight-gradient product reads: it may still be running (on the side stream)
+  // while the next layer's are written
+  for (int p = 0; p < 2; ++p) {
+    w.t_dy[p] = take(Rmax * D.d * D.E);
+    w.t_dh[p] = take(Rmax * D.d * D.E);
+    w.t_dgu[p] = take(Rmax * 2 * D.h * D.E);
+    w.t_dqkv[p] = take(Rmax * D.nq * D.E);
+  }
   w.t_d2 = take(Rmax * D.d * D.E);
   w.t_da = take(Rmax * D.h * D.E);
-  w.t_dgu = take(Rmax * 2 * D.h * D.E);
-  w.t_dqkv = take(Rmax * D.nq * D.E);
   w.t_delta = take(Rmax * D.H * sizeof(float));
   w.rope = take((size_t)D.T * (D.hd / 2) * 2 * sizeof(float));   // cos, sin per (position, pair)
   if (c.has_head) {
@@ -121,6 +125,12 @@ struct sp_ctx {
   int n_mb_max, n_visits_max;
   char* base;
   float* rope_tab;   // inside the workspace, filled at creation
+  // weight-gradient products run on a stream of their own, beside the chain that carries the activation
+  // gradient down the layers; events order the two (ready: input written; done: input no longer read)
+  hipStream_t side;
+  hipEvent_t ready[4], done[2][4], joined;
+  bool done_set[2][4];
+  bool use_side;     // false: weight gradients run in line on the caller's stream
   Carve w;
   size_t arena_top;
   std::vector<Record> records;
@@ -198,6 +208,19 @@ int sp_create(const sp_cfg* cfg, void* hip_stream, int n_mb_max, int n_visits_ma
     delete c;
     return fail(SP_ENOMEM, std::string("hipMalloc of the workspace failed: ") + hipGetErrorString(e));
   }
+  c->side = nullptr;
+  c->use_side = true;
+  e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
+  for (int i = 0; i < 4 && e == hipSuccess; ++i) {
+    e = hipEventCreateWithFlags(&c->ready[i], hipEventDisableTiming);
+    for (int p = 0; p < 2 && e == hipSuccess; ++p) e = hipEventCreateWithFlags(&c->done[p][i], hipEventDisableTiming);
+  }
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&c->joined, hipEventDisableTiming);
+  if (e != hipSuccess) {
+    (void)hipFree(c->base);
+    delete c;
+    return hip_fail((int)e, "side stream / events");
+  }
   c->rope_tab = (float*)at(c, c->w.rope);
   rope_table(c->stream, (int)Dims(*cfg).T, (int)Dims(*cfg).hd, cfg->rope_theta, c->rope_tab);
   e = hipGetLastError();
@@ -213,10 +236,23 @@ int sp_create(const sp_cfg* cfg, void* hip_stream, int n_mb_max, int n_visits_ma
 int sp_destroy(sp_ctx* ctx) {
   if (!ctx) return SP_OK;
   hipError_t e = hipStreamSynchronize(ctx->stream);
+  (void)hipStreamSynchronize(ctx->side);
+  for (int i = 0; i < 4; ++i) {
+    (void)hipEventDestroy(ctx->ready[i]);
+    for (int p = 0; p < 2; ++p) (void)hipEventDestroy(ctx->done[p][i]);
+  }
+  (void)hipEventDestroy(ctx->joined);
+  (void)hipStreamDestroy(ctx->side);
   hipError_t e2 = hipFree(ctx->base);
   delete ctx;
   if (e != hipSuccess) return hip_fail((int)e, "hipStreamSynchronize");
   if (e2 != hipSuccess) return hip_fail((int)e2, "hipFree");
+  return SP_OK;
+}
+
+int sp_set_side_stream(sp_ctx* ctx, int enabled) {
+  if (!ctx) return fail(SP_EINVAL, "ctx is null");
+  ctx->use_side = enabled != 0;
   return SP_OK;
 }
 
@@ -340,35 +376,63 @@ int sp_stage_bwd(sp_ctx* ctx, int stage, const void* params, void* dact_pool, co
   const int loc = stage - cfg.local_stage_begin;
   const int Bg = (int)(n_group * D.B);
 
-  char* dy = at(ctx, ctx->w.t_d0);
-  char* dh = at(ctx, ctx->w.t_d1);
   char* t = at(ctx, ctx->w.t_d2);
   char* da = at(ctx, ctx->w.t_da);
-  char* dgu = at(ctx, ctx->w.t_dgu);
-  char* dqkv = at(ctx, ctx->w.t_dqkv);
   float* delta = (float*)at(ctx, ctx->w.t_delta);
+  hipStream_t side = ctx->use_side ? ctx->side : s;
+  for (int p = 0; p < 2; ++p)
+    for (int i = 0; i < 4; ++i) ctx->done_set[p][i] = false;
+  // weight gradient k of the layer (0: down, 1: gate/up, 2: output, 3: qkv) on the side stream, once its input
+  // (just written on the main stream) is ready; `done` marks when that input may be overwritten
+  auto side_dw = [&](int k, int par, int64_t M, int64_t N, const void* A, const void* B, float* C) -> int {
+    SP_HIP(hipEventRecord(ctx->ready[k], s));
+    SP_HIP(hipStreamWaitEvent(side, ctx->ready[k], 0));
+    int r = gemm(side, dt, 2, M, N, R, A, B, C, nullptr);
+    if (r) return r;
+    SP_HIP(hipEventRecord(ctx->done[par][k], side));
+    ctx->done_set[par][k] = true;
+    return SP_OK;
+  };
+  auto wait_done = [&](int k, int par) -> int {
+    if (ctx->done_set[par][k]) SP_HIP(hipStreamWaitEvent(s, ctx->done[par][k], 0));
+    return SP_OK;
+  };
 
-  gather_slots(s, dt, dact_pool, sl, D.Nmb, (int)D.d, dy);
-  for (int l = cfg.layers_per_stage - 1; l >= 0; --l) {
+  gather_slots(s, dt, dact_pool, sl, D.Nmb, (int)D.d, at(ctx, ctx->w.t_dy[0]));
+  int par = 0;
+  for (int l = cfg.layers_per_stage - 1; l >= 0; --l, par ^= 1) {
     const LayerOff& w = ctx->L.layers[(size_t)loc * cfg.layers_per_stage + l];
     const LayerSaved& ls = rec.layers[l];
+    char* dy = at(ctx, ctx->w.t_dy[par]);
+    char* dy_next = at(ctx, ctx->w.t_dy[par ^ 1]);
+    char* dh = at(ctx, ctx->w.t_dh[par]);
+    char* dgu = at(ctx, ctx->w.t_dgu[par]);
+    char* dqkv = at(ctx, ctx->w.t_dqkv[par]);
     // feed-forward: y = h + a Wd^T
-    if ((rc = gemm(s, dt, 2, D.d, D.h, R, dy, ls.a, grads + w.wd, nullptr))) return rc;
+    if ((rc = side_dw(0, par, D.d, D.h, dy, ls.a, grads + w.wd))) return rc;
     if ((rc = gemm(s, dt, 1, R, D.h, D.d, dy, P(ctx, params, w.wd), da, nullptr))) return rc;
+    if ((rc = wait_done(1, par))) return rc;
     swiglu_bwd(s, dt, da, ls.gu, R, (int)D.h, dgu);
-    if ((rc = gemm(s, dt, 2, 2 * D.h, D.d, R, dgu, ls.hn, grads + w.wgu, nullptr))) return rc;
+    if ((rc = side_dw(1, par, 2 * D.h, D.d, dgu, ls.hn, grads + w.wgu))) return rc;
     if ((rc = gemm(s, dt, 1, R, D.d, 2 * D.h, dgu, P(ctx, params, w.wgu), t, nullptr))) return rc;
+    if ((rc = wait_done(2, par))) return rc;
     rmsnorm_bwd(s, dt, t, ls.h, P(ctx, params, w.g2), ls.rstd2, dy, R, (int)D.d, dh, grads + w.g2);
     // attention: h = x + o Wo^T
-    if ((rc = gemm(s, dt, 2, D.d, D.d, R, dh, ls.o, grads + w.wo, nullptr))) return rc;
+    if ((rc = side_dw(2, par, D.d, D.d, dh, ls.o, grads + w.wo))) return rc;
     if ((rc = gemm(s, dt, 1, R, D.d, D.d, dh, P(ctx, params, w.wo), t, nullptr))) return rc;
+    if ((rc = wait_done(3, par))) return rc;
     if ((rc = attention_bwd(s, dt, Bg, (int)D.T, (int)D.H, (int)D.Hkv, (int)D.hd, ls.qkv, ls.o, ls.lse, t, dqkv, delta,
                             ctx->rope_tab, cfg.rope_theta)))
       return rc;
-    if ((rc = gemm(s, dt, 2, D.nq, D.d, R, dqkv, ls.xn, grads + w.wqkv, nullptr))) return rc;
+    if ((rc = side_dw(3, par, D.nq, D.d, dqkv, ls.xn, grads + w.wqkv))) return rc;
     if ((rc = gemm(s, dt, 1, R, D.d, D.nq, dqkv, P(ctx, params, w.wqkv), t, nullptr))) return rc;
-    rmsnorm_bwd(s, dt, t, ls.x, P(ctx, params, w.g1), ls.rstd1, dh, R, (int)D.d, dy, grads + w.g1);
+    if ((rc = wait_done(0, par ^ 1))) return rc;   // the layer above may still read its dy
+    rmsnorm_bwd(s, dt, t, ls.x, P(ctx, params, w.g1), ls.rstd1, dh, R, (int)D.d, dy_next, grads + w.g1);
   }
+  char* dy = at(ctx, ctx->w.t_dy[par]);
+  // the caller's stream continues only after every weight gradient has landed
+  SP_HIP(hipEventRecord(ctx->joined, side));
+  SP_HIP(hipStreamWaitEvent(s, ctx->joined, 0));
   scatter_slots(s, dt, dy, sl, D.Nmb, (int)D.d, dact_pool);
   SP_HIP(hipGetLastError());
   rec.live = false;

@@ -15,10 +15,12 @@ def n_visits(cfg, paths, lens):
     return int(sum(1 for mb in range(len(lens)) for s in paths[mb, :lens[mb]] if lo <= s < hi))
 
 
-def run(cfg, named, paths, lens, tokens=None, targets=None, x_in=None, dy_in=None, whole_call=True, regroup=None):
+def run(cfg, named, paths, lens, tokens=None, targets=None, x_in=None, dy_in=None, whole_call=True, regroup=None,
+        side_stream=True):
     """Same contract as the CPU checker's run_paths.  whole_call: use sp_run_paths when the node holds the
     whole model; otherwise (or for stage shares) walk the route plan through the stage entry points.
-    regroup: optional function plan -> plan (e.g. split every group into single microbatches)."""
+    regroup: optional function plan -> plan (e.g. split every group into single microbatches).
+    side_stream: weight-gradient products beside the main chain (the default) or in line."""
     dev = "cuda"
     dt = sp.torch_dtype(cfg)
     n_mb = len(lens)
@@ -28,6 +30,7 @@ def run(cfg, named, paths, lens, tokens=None, targets=None, x_in=None, dy_in=Non
     grads = torch.zeros(params.numel(), dtype=torch.float32, device=dev)
     whole = cfg["has_embed"] and cfg["has_head"] and cfg["local_stage_count"] == cfg["n_stages"]
     ctx = sp.Context(cfg, n_mb, max(1, n_visits(cfg, paths, lens)))
+    ctx.set_side_stream(side_stream)
     out = {}
     try:
         tok = None if tokens is None else torch.from_numpy(np.ascontiguousarray(tokens, np.int32).reshape(-1)).to(dev)

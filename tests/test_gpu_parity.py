@@ -236,3 +236,18 @@ def test_call_order_and_argument_errors():
         bad[0] = [1, 0, 2, 3]
         run(cfg, synth.make_params(cfg, 1), bad, np.array([4] * 5, np.int32), *synth.make_tokens(cfg, 1))
     assert e.value.code == -2
+
+
+def test_side_stream_changes_nothing_but_the_order_of_float_additions():
+    # weight gradients beside the main chain or in line: same results up to the order of the atomic adds
+    cfg = synth.shrink(synth.CONFIGS["c3"], seq_len=256, n_mb=4, layers_per_stage=3)
+    paths, lens, stage = synth.stage_share_paths("c3")
+    paths, lens = paths[:4], lens[:4]
+    cfg["local_stage_begin"], cfg["local_stage_count"] = stage, 1
+    named = {k: round_bf16(v) for k, v in synth.make_params(cfg, 12).items()}
+    x = round_bf16(synth.make_activations(cfg, 12)); dy = round_bf16(synth.make_upstream_grad(cfg, 12))
+    a = run(cfg, named, paths, lens, x_in=x, dy_in=dy, side_stream=True)
+    b = run(cfg, named, paths, lens, x_in=x, dy_in=dy, side_stream=False)
+    np.testing.assert_array_equal(a["dx"], b["dx"])
+    for k in a["grads"]:
+        assert relerr(a["grads"][k], b["grads"][k]) < 1e-5, k
