@@ -20,6 +20,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
+# HBM-side bytes per launch of the weight-gradient product at the default workload, from rocprofv3 --pmc
+# FETCH_SIZE (x 1.998, the factor a plain copy of known size gives) + WRITE_SIZE (x 1.000); see profiles/.
+# Valid for the kernel as it was when the counters were taken: set to None when k_gemm_mfma changes.
+GEMM_TN_C3_TRAFFIC_BYTES = 833.5e6
 
 
 def flops_per_token_layer(cfg):
@@ -268,7 +272,9 @@ def main():
         roof = dict(bound="mfma", kernel={"gemm_nt": "k_gemm_mfma<0>", "gemm_nn": "k_gemm_mfma<1>",
                                           "gemm_tn": "k_gemm_mfma<2>"}[dom],
                     achieved=round(achieved, 1), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
-                    frac=round(achieved / PEAK_BF16_TFLOPS, 4), traffic=None,
+                    frac=round(achieved / PEAK_BF16_TFLOPS, 4),
+                    traffic=(GEMM_TN_C3_TRAFFIC_BYTES if dom == "gemm_tn" and args.config == "c3" and not args.one_group
+                             else None),
                     avg_launch_ms=round(p["ms"] / p["launches"], 4), launches_per_step=p["launches"] // args.steps,
                     share_of_step=round(p["ms"] / args.steps / (sec * 1e3), 3))
     kernels = {k: dict(ms_per_step=round(v["ms"] / args.steps, 3),
