@@ -1,4 +1,6 @@
-// bf16 matrix products on the CDNA4 matrix cores (v_mfma_f32_32x32x16_bf16), float accumulation.
+// bf16 matrix products on the CDNA4 matrix cores, float accumulation.  Ops 0 and 1 use
+// v_mfma_f32_16x16x32_bf16, which on random data sustains more flops per watt than the 32x32x16 form (the chip
+// is power-limited here); op 2 keeps v_mfma_f32_32x32x16_bf16, whose accumulator layout gives wider atomics.
 //
 // One workgroup of 8 wavefronts owns a 256x256 tile of the output and walks the reduction
 // dimension in steps of 64.  Operand tiles go from memory straight into LDS (buffer loads with the LDS
@@ -19,9 +21,9 @@
 //   op 0  C[M,N]  = A[M,K] B[N,K]^T (+R)   A, B k-contiguous
 //   op 1  C[M,N]  = A[M,K] B[K,N]          B k-strided
 //   op 2  C[M,N] += A[K,M]^T B[K,N]        both k-strided; float output, added atomically: the k-steps
-//                                          of all tiles are dealt out in equal runs, one per CU, whatever
-//                                          the number of tiles (a weight gradient has few tiles and a
-//                                          long reduction)
+//                                          of every tile are cut into a whole number of equal runs, one
+//                                          workgroup each, so that the rounds of workgroups are full (a
+//                                          weight gradient has few tiles and a long reduction)
 //
 // For bf16 outputs the MFMA is issued with the tile of B as its row operand and the tile of A as its
 // column operand, so a lane's accumulator holds 4 consecutive output columns of one output row; they go
@@ -38,6 +40,7 @@ namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) int i32x4;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
@@ -69,10 +72,13 @@ constexpr uint32_t kPastEnd = 0x80000000u;      // no descriptor is this large
 // Instruction j fills the tile's 16-byte chunks (8j + wave) * 64 + lane.
 //   k-contiguous tile: [256 rows][64 k], 8 chunks per row; the chunk at position p of a row holds the row's
 //     chunk p ^ ((row >> 1) & 7): the 16 rows a ds_read_b128 touches then fall in 16 different bank groups.
-//   k-strided tile: [64 k][256 x], 32 chunks per k row; position p of k row k holds chunk p ^ ((k & 3) << 2):
-//     the 4 k rows x 4 chunks a transpose read touches fall in 16 different bank groups.
+//   k-strided tile: [64 k][256 x], 32 chunks per k row; position p of k row k holds chunk p ^ kkey(k).
+//     For 16-wide fragments kkey(k) = ((k & 3) | ((k >> 3) & 1) << 2) << 1: the 8 k rows x 32 bytes that 32
+//     lanes of a transpose read touch (rows k0..k0+3 and k0+8..k0+11) fall in 8 different 32-byte bank groups.
+//     For 32-wide fragments (W32, the weight-gradient product) kkey(k) = (k & 3) << 2: the 4 k rows x 4 chunks
+//     that 32 lanes touch fall in 16 different bank groups.
 // The permutation is applied on the memory side: a lane fetches the chunk that belongs at its position.
-template <bool KSTRIDED>
+template <bool KSTRIDED, bool W32>
 struct Operand {
   const char* base;    // first byte of the tile's rows (k-contiguous) or of its first x (k-strided), at k = 0
   int64_t left;        // bytes from base to the end of the operand
@@ -90,7 +96,8 @@ struct Operand {
     for (int j = 0; j < 4; ++j) {
       const int q = (8 * j + wave) * 64 + lane;
       if (KSTRIDED) {
-        const int krow = q >> 5, pos = q & 31, c = pos ^ ((krow & 3) << 2);
+        const int krow = q >> 5, pos = q & 31;
+        const int c = pos ^ (W32 ? (krow & 3) << 2 : ((krow & 3) | (((krow >> 3) & 1) << 2)) << 1);
         voff[j] = ((uint32_t)krow * ld + c * 8) * 2u;
       } else {
         const int row = q >> 3, pos = q & 7, c = pos ^ ((row >> 1) & 7);
@@ -114,10 +121,37 @@ struct Operand {
   }
 };
 
-// MFMA fragment of tile row `row_base + lane % 32` for k-step ks (16 k): 8 consecutive k, starting at
+// MFMA operand fragment (v_mfma_f32_16x16x32_bf16: lane l holds row l % 16, k = (l / 16) * 8 .. + 7) of tile rows
+// row_base .. row_base + 15 for the k32-th group of 32 k of the step.  row_base is a multiple of 16.
+template <bool KSTRIDED>
+__device__ __forceinline__ bf16x8 read_frag(const char* tile, int row_base, int k32, int lane) {
+  if (!KSTRIDED) {
+    const int lr = lane & 15, kg = lane >> 4;
+    // chunk 4 k32 + kg permuted by the row's key; k32 enters by XOR with k32 * 64
+    const int lane_off = lr * 128 + ((kg ^ ((lr >> 1) & 7)) << 4);
+    return *reinterpret_cast<const bf16x8*>(tile + row_base * 128 + (lane_off ^ (k32 * 64)));
+  } else {
+    // Two transpose reads.  Within a group of 16 lanes, lane s addresses k row s/4 and the 8-byte piece s%4 of
+    // the group's 32 bytes (16 x), and receives x = s, 4 consecutive k.  Group g = lane/16 takes k rows
+    // 8g .. 8g+3, then 8g+4 .. 8g+7; both have the same kkey: (s/4) | (g & 1) << 2, shifted left by one.
+    const int g = lane >> 4, s = lane & 15;
+    const int key = ((s >> 2) | ((g & 1) << 2)) << 1;
+    const int lane_off = (g * 8 + (s >> 2)) * 512 + (key << 4) + (((s & 3) >> 1) << 4) + (s & 1) * 8;
+    const char* p = tile + k32 * 32 * 512 + (lane_off ^ (row_base * 2));   // row_base * 2: a multiple of 32 bytes
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * 512));
+    typedef __attribute__((ext_vector_type(8))) short s16x8;
+    s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8, v);
+  }
+}
+
+// The same for v_mfma_f32_32x32x16_bf16 (the weight-gradient product keeps this form: its accumulator layout
+// gives atomics that cover 128 contiguous bytes).  Fragment of tile row `row_base + lane % 32` for k-step ks (16 k): 8 consecutive k, starting at
 // ks*16 + (lane/32)*8.  row_base is a multiple of 32.
 template <bool KSTRIDED>
-__device__ __forceinline__ bf16x8 read_frag(const char* tile, int row_base, int ks, int lane) {
+__device__ __forceinline__ bf16x8 read_frag32(const char* tile, int row_base, int ks, int lane) {
   if (!KSTRIDED) {
     const int lr = lane & 31, hh = lane >> 5;
     // chunk 2 ks + hh permuted by the row's key; ks enters by XOR with ks * 32
@@ -177,36 +211,65 @@ __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__
   const int kb = ks0 * BK, kend = min(K, ks1 * BK);
   const int nk = ks1 - ks0;
 
-  Operand<AS> opa;
-  Operand<BS> opb;
+  constexpr bool W32 = OP == 2;   // which MFMA form (see read_frag32)
+  Operand<AS, W32> opa;
+  Operand<BS, W32> opb;
   opa.init(A, AS ? K : M, AS ? M : K, m0, wave, lane);
   opb.init(B, BS ? K : N, BS ? N : K, n0, wave, lane);
 
-  // acc[j][i]: MFMA rows = 32 output columns n (i of 2), MFMA columns = 32 output rows m (j of 4)
-  f32x16 acc[4][2];
+  // OP 0/1: acc[j][i] = 16 output rows m (j of 8) x 16 output columns n (i of 4) of the wavefront's 128 x 64.
+  // OP 2: acc32[j][i] = 32 rows (j of 4) x 32 columns (i of 2).
+  f32x4 acc[W32 ? 1 : 8][W32 ? 1 : 4];
+  f32x16 acc32[W32 ? 4 : 1][W32 ? 2 : 1];
+  if (W32) {
 #pragma unroll
-  for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[j][i][r] = 0.f;
+        for (int r = 0; r < 16; ++r) acc32[W32 ? j : 0][W32 ? i : 0][r] = 0.f;
+  } else {
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[W32 ? 0 : j][W32 ? 0 : i][r] = 0.f;
+  }
 
   auto compute = [&](const char* base) {
     const char* ta = base;
     const char* tb = base + kTileBytes;
+    if (W32) {
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 fa[4], fb[2];
+      for (int ks = 0; ks < BK / 16; ++ks) {
+        bf16x8 fa[4], fb[2];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) fa[j] = read_frag<AS>(ta, wm * 128 + j * 32, ks, lane);
+        for (int j = 0; j < 4; ++j) fa[j] = read_frag32<AS>(ta, wm * 128 + j * 32, ks, lane);
 #pragma unroll
-      for (int i = 0; i < 2; ++i) fb[i] = read_frag<BS>(tb, wn * 64 + i * 32, ks, lane);
+        for (int i = 0; i < 2; ++i) fb[i] = read_frag32<BS>(tb, wn * 64 + i * 32, ks, lane);
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < 4; ++j)
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
-          acc[j][i] = OP == 2 ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[j], fb[i], acc[j][i], 0, 0, 0)
-                              : __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[i], fa[j], acc[j][i], 0, 0, 0);
+          for (int i = 0; i < 2; ++i)
+            acc32[W32 ? j : 0][W32 ? i : 0] =
+                __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[j], fb[i], acc32[W32 ? j : 0][W32 ? i : 0], 0, 0, 0);
+      }
+    } else {
+#pragma unroll
+      for (int k32 = 0; k32 < BK / 32; ++k32) {
+        bf16x8 fa[8], fb[4];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) fa[j] = read_frag<AS>(ta, wm * 128 + j * 16, k32, lane);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) fb[i] = read_frag<BS>(tb, wn * 64 + i * 16, k32, lane);
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            acc[W32 ? 0 : j][W32 ? 0 : i] =
+                __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[i], fa[j], acc[W32 ? 0 : j][W32 ? 0 : i], 0, 0, 0);
+      }
     }
   };
   // step t of the reduction goes to stage t & 1
@@ -229,9 +292,9 @@ __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__
     landed_barrier();
   }
 
-  // ---- epilogue.  Accumulator r of lane l: output row m = lane%32, output column n = (r/4)*8 + (l/32)*4 + r%4
-  // of its 32x32 tile, i.e. 4 consecutive columns per group of 4 registers.
-  const int lm = lane & 31, hh = lane >> 5;
+  // ---- epilogue.  With the tile of B as the MFMA's row operand (OP 0/1), accumulator r of lane l is output
+  // row m = l % 16, output column n = (l / 16) * 4 + r of its 16x16 block: 4 consecutive columns.
+  const int lm = lane & 15, kg = lane >> 4;
   if (OP == 2) {
     // float output, accumulated in place.  Here the tile of A is the MFMA's row operand: accumulator r of
     // lane l is output row (r/4)*8 + (l/32)*4 + r%4, column l%32, so a wavefront's atomic covers 128
@@ -241,29 +304,27 @@ __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__
     for (int j = 0; j < 4; ++j)
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
-        const int col = n0 + wn * 64 + i * 32 + lm;
+        const int col = n0 + wn * 64 + i * 32 + (lane & 31);
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int row = m0 + wm * 128 + j * 32 + (r >> 2) * 8 + hh * 4 + (r & 3);
+          const int row = m0 + wm * 128 + j * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
           if (row < M && col < N) {
             float* p = C + (int64_t)row * N + col;
-            unsafeAtomicAdd(p, acc[j][i][r]);
+            unsafeAtomicAdd(p, acc32[W32 ? j : 0][W32 ? i : 0][r]);
           }
         }
       }
   } else {
     // all wavefronts are past the last barrier of the loop: the operand buffers are free
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < 8; ++j)
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          uint2 w;
-          w.x = pack_bf16(acc[j][i][4 * g], acc[j][i][4 * g + 1]);
-          w.y = pack_bf16(acc[j][i][4 * g + 2], acc[j][i][4 * g + 3]);
-          *reinterpret_cast<uint2*>(smem + (wm * 128 + j * 32 + lm) * kCRowBytes + (wn * 64 + i * 32 + g * 8 + hh * 4) * 2) = w;
-        }
+      for (int i = 0; i < 4; ++i) {
+        uint2 w;
+        w.x = pack_bf16(acc[W32 ? 0 : j][W32 ? 0 : i][0], acc[W32 ? 0 : j][W32 ? 0 : i][1]);
+        w.y = pack_bf16(acc[W32 ? 0 : j][W32 ? 0 : i][2], acc[W32 ? 0 : j][W32 ? 0 : i][3]);
+        *reinterpret_cast<uint2*>(smem + (wm * 128 + j * 16 + lm) * kCRowBytes + (wn * 64 + i * 16 + kg * 4) * 2) = w;
+      }
     __syncthreads();
     bf16* C = reinterpret_cast<bf16*>(Cv);
     const bool add = OP == 0 && Rr != nullptr;
