@@ -114,8 +114,9 @@ int sp_make_paths(int n_stages, int n_mb, int skip_num, int skip_den, int allow_
  * indices in range, order rule.  SP_EPATH names the first violation through sp_strerror. */
 int sp_check_paths(const sp_cfg* cfg, const int32_t* paths, const int32_t* len, int n_mb);
 
-/* Route plan: for every path position pos and stage st, the microbatches with paths[mb][pos]==st,
- * restricted to local stages.  Groups are emitted by increasing pos, then stage; the forward pass
+/* Route plan (section "Partial and Reordered Pipelining": several microbatches may share a path, and a
+ * stage serves whoever arrives): for every path position pos and stage st, the microbatches with
+ * paths[mb][pos]==st, restricted to local stages.  Groups are emitted by increasing pos, then stage; the forward pass
  * runs them in this order, the backward pass in reverse.  group_pos/group_stage/group_begin: host
  * int32 [cap_groups] (+1 for group_begin); group_mb: host int32 [n_mb*n_stages]. */
 int sp_route_plan(const sp_cfg* cfg, const int32_t* paths, const int32_t* len, int n_mb, int32_t* group_pos,
@@ -142,32 +143,39 @@ int sp_set_side_stream(sp_ctx* ctx, int enabled);
 /* Forgets every saved forward (e.g. after an aborted iteration). */
 int sp_reset(sp_ctx* ctx);
 
-/* x[row, :] = embed[token[row], :] for n_mb microbatches (the front of stage 0).
+/* x[row, :] = embed[token[row], :] for n_mb microbatches (the front of stage 0, which every path opens
+ * with: constraint CC1 of "Guideline for Partial Pipelining Scheduler").
  * tokens: int32 [n_mb * N_mb]; act_pool: [n_mb][N_mb][dim] in cfg->dtype. */
 int sp_embed_fwd(sp_ctx* ctx, const void* params, const int32_t* tokens, int n_mb, void* act_pool);
 /* grads[embed][token[row], :] += dact[row, :]. */
 int sp_embed_bwd(sp_ctx* ctx, const int32_t* tokens, const void* dact_pool, int n_mb, float* grads);
 
-/* Forward of local stage `stage` (global index) for the group of microbatches mb_idx[0..n_group)
+/* Section "Partial pipeline schedule": a microbatch runs only the stages on its path; a stage is a run of
+ * consecutive LLaMa decoder layers ("System Setting"; appendix "Model Configurations").
+ * Forward of local stage `stage` (global index) for the group of microbatches mb_idx[0..n_group)
  * (host int32, distinct slot numbers of act_pool), in place on their slots; every other slot is
  * untouched (that is the skip).  The layers' intermediate results are kept inside ctx, keyed by
  * (stage, group), until the matching sp_stage_bwd. */
 int sp_stage_fwd(sp_ctx* ctx, int stage, const void* params, void* act_pool, const int32_t* mb_idx, int n_group);
 
-/* Backward of the same group (same stage, same mb_idx in the same order; SP_ESTATE otherwise):
+/* The backward pass visits the same stages in reverse ("Partial pipeline schedule"); gradients of all
+ * microbatches are summed before any update ("System Setting").
+ * Backward of the same group (same stage, same mb_idx in the same order; SP_ESTATE otherwise):
  * dact_pool slots hold dL/d(output) on entry and dL/d(input) on return; parameter gradients are
  * added into grads (float, parameter layout). */
 int sp_stage_bwd(sp_ctx* ctx, int stage, const void* params, void* dact_pool, const int32_t* mb_idx, int n_group,
                  float* grads);
 
-/* Final norm, output head and next-token cross-entropy for all n_mb microbatches, forward and
+/* The loss is taken where the path closes, on stage 0's node ("Allocating Nodes to Stages": closed loop).
+ * Final norm, output head and next-token cross-entropy for all n_mb microbatches, forward and
  * backward at once: loss_mb[mb] = mean over the targets >= 0 of microbatch mb; the iteration loss
  * is their mean, so dact_pool receives d(mean)/d(act) = d(loss_mb)/d(act) / n_mb.  targets: int32
  * [n_mb * N_mb], -1 = ignored.  loss_mb: device float [n_mb].  grads: += for gf and whead. */
 int sp_head_fwd_bwd(sp_ctx* ctx, const void* params, const void* act_pool, const int32_t* targets, int n_mb,
                     float* loss_mb, void* dact_pool, float* grads);
 
-/* Whole model on this node (all stages local, embedding and head held): embeds, walks the route
+/* One iteration of partial pipelining with every stage on this node ("Partial pipeline schedule").
+ * Whole model on this node (all stages local, embedding and head held): embeds, walks the route
  * plan of the given paths (host arrays, checked against cfg->path_flags), takes the loss, walks
  * the plan backwards, and returns the iteration loss.  grads is zeroed by the call.  loss_host:
  * host float[1]; loss_mb_host: host float [n_mb] or NULL.  Waits for the stream. */
@@ -175,7 +183,8 @@ int sp_run_paths(sp_ctx* ctx, const void* params, const int32_t* tokens, const i
                  const int32_t* paths, const int32_t* len, int n_mb, float* loss_host, float* loss_mb_host,
                  float* grads);
 
-/* Matrix products used by the stages, exposed for unit tests and roofline measurement.
+/* Matrix products used by the stages (the projections of the decoder layer and their gradients), exposed
+ * for unit tests and roofline measurement.
  *   op 0: C[M,N]  = A[M,K] * B[N,K]^T  (+ R[M,N] if R != NULL)      C, R in cfg dtype
  *   op 1: C[M,N]  = A[M,K] * B[K,N]                                  C in cfg dtype
  *   op 2: C[M,N] += A[K,M]^T * B[K,N]                                C float
@@ -183,7 +192,9 @@ int sp_run_paths(sp_ctx* ctx, const void* params, const int32_t* tokens, const i
 int sp_gemm(void* hip_stream, int dtype, int op, int M, int N, int K, const void* A, const void* B, void* C,
             const void* R);
 
-/* Causal attention used by the stages, exposed for unit tests and roofline measurement.
+/* Causal softmax attention with grouped kv heads as used by the stages (per sequence and head:
+ * softmax(q k^T / sqrt(hd) + causal mask) v, and its gradients), exposed for unit tests and roofline
+ * measurement.
  * qkv: [B*T][(H + 2*Hkv)*hd] rows of query|key|value; o: [B*T][H*hd]; lse: float [B][H][T].
  * Backward: do_ like o; dqkv like qkv (overwritten). */
 int sp_attention_fwd(void* hip_stream, int dtype, int B, int T, int H, int Hkv, int hd, const void* qkv, void* o,
