@@ -122,6 +122,49 @@ int sp_check_paths(const sp_cfg* cfg, const int32_t* paths, const int32_t* len, 
 int sp_route_plan(const sp_cfg* cfg, const int32_t* paths, const int32_t* len, int n_mb, int32_t* group_pos,
                   int32_t* group_stage, int32_t* group_begin, int32_t* group_mb, int cap_groups, int* n_groups);
 
+/* Path scheduler (sections "Partial and Reordered Pipelining" and "Path finding", appendix "Detailed Path
+ * Selection Algorithm"): for the first wave of microbatches (agents), which node of which stage each visits
+ * and when, so that the slowest agent's end-to-end latency is small under the paper's constraints:
+ *   CC1 an agent starts (and ends: the loss is taken there) on its node of stage 0;
+ *   CC2 stages in increasing order with at most one exchange of two neighbouring stages (strict_swap != 0:
+ *       the exchanged stages are consecutive stages of the model);
+ *   CC3 every stage but the first is left out by the same number of agents, up to one;
+ *   TC1 at most mem_limit paths through a node;  TC2 no two agents on one node at the same time (forward
+ *       stays; links are full duplex and never conflict).
+ * Conflict-based search: a best-first search per agent over (node, visited stages) with time as cost, and
+ * a tree of per-agent "may not occupy node n during [t0, t1)" constraints above it, with the paper's greedy
+ * rules (HR1: n_solutions solutions that honour CC1-CC3 are collected first, 32 if n_solutions <= 0; HR2: the
+ * slowest quarter of the agents, and the slowest path through an over-full node, are never constrained; HR3:
+ * of two colliding agents the faster one waits; if their latencies differ by less than delta both choices
+ * are tried).  It is a
+ * heuristic: the result is valid, not provably optimal.
+ * All arrays are host arrays.  node_stage [n_nodes]; compute_fwd / compute_bwd [n_nodes]: seconds for one
+ * microbatch; comm [n_nodes][n_nodes]: seconds to move one microbatch's activations from row to column node;
+ * start_node [n_agents] (nodes of stage 0); n_keep [n_agents]: stages on the agent's path, stage 0 included
+ * (s * (1 - k), rounded by the caller).  An agent's latency: forward stays and transfers, return to the
+ * start node, then the backward pass along the reversed path without waiting (only the first forward pass
+ * is scheduled, as in the paper).
+ * Outputs (host): path_nodes, path_stages [n_agents][n_stages] padded with -1 (path_stages feeds
+ * sp_run_paths / sp_check_paths); len [n_agents]; arrive [n_agents][n_stages] (start of each forward stay,
+ * may be null); e2e [n_agents] and max_e2e (may be null).  SP_EPATH: no conflict-free solution found within
+ * max_expansions (20000 if <= 0) constraint-tree expansions; SP_EINVAL: bad sizes, a start node outside
+ * stage 0, a stage without nodes, negative times. */
+typedef struct sp_sched_problem {
+  int32_t n_stages, n_nodes, n_agents;
+  int32_t mem_limit;   /* m of TC1 */
+  int32_t strict_swap; /* CC2: exchanged stages must be consecutive */
+  int32_t n_solutions, max_expansions;
+  float delta;
+  const int32_t* node_stage;
+  const float* compute_fwd;
+  const float* compute_bwd;
+  const float* comm;
+  const int32_t* start_node;
+  const int32_t* n_keep;
+} sp_sched_problem;
+int sp_schedule_paths(const sp_sched_problem* problem, int32_t* path_nodes, int32_t* path_stages, int32_t* len,
+                      float* arrive, float* e2e, float* max_e2e);
+
 const char* sp_strerror(int status);
 
 /* ---- device ------------------------------------------------------------------------------------ */

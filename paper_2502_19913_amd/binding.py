@@ -20,7 +20,7 @@ SP_F32, SP_BF16 = 0, 1
 SP_STRICT_CC, SP_SWAP_ANY_GAP, SP_ALLOW_ANY_ORDER = 0, 1, 2
 
 EXPORTS = ["sp_param_count", "sp_param_layout", "sp_workspace_bytes", "sp_make_paths", "sp_check_paths",
-           "sp_route_plan", "sp_strerror", "sp_create", "sp_destroy", "sp_reset", "sp_set_side_stream", "sp_embed_fwd", "sp_embed_bwd",
+           "sp_route_plan", "sp_schedule_paths", "sp_strerror", "sp_create", "sp_destroy", "sp_reset", "sp_set_side_stream", "sp_embed_fwd", "sp_embed_bwd",
            "sp_stage_fwd", "sp_stage_bwd", "sp_head_fwd_bwd", "sp_run_paths", "sp_eval_paths", "sp_gemm", "sp_attention_fwd",
            "sp_attention_bwd", "sp_optim_workspace_bytes", "sp_optim_step", "sp_prof_begin", "sp_prof_end"]
 
@@ -156,6 +156,31 @@ def unpack(cfg: dict, flat) -> Dict[str, np.ndarray]:
         a = host[off:off + rows * cols]
         out[name] = a.reshape(cols) if rows == 1 and name.split(".")[-1] in ("g1", "g2", "gf") else a.reshape(rows, cols)
     return out
+
+
+class SpSchedProblem(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_stages", "n_nodes", "n_agents", "mem_limit", "strict_swap", "n_solutions",
+                                         "max_expansions")] + [("delta", C.c_float)] + \
+               [(n, C.c_void_p) for n in ("node_stage", "compute_fwd", "compute_bwd", "comm", "start_node", "n_keep")]
+
+
+def schedule_paths(node_stage, compute_fwd, compute_bwd, comm, start_node, n_keep, mem_limit, strict_swap=True,
+                   n_solutions=32, max_expansions=20000, delta=0.0) -> dict:
+    """Path scheduler (host only): returns path_nodes, path_stages [A][s] (-1 padded), len, arrive, e2e, max_e2e."""
+    ns = np.ascontiguousarray(node_stage, np.int32)
+    cf = np.ascontiguousarray(compute_fwd, np.float32); cb = np.ascontiguousarray(compute_bwd, np.float32)
+    cm = np.ascontiguousarray(comm, np.float32)
+    st = np.ascontiguousarray(start_node, np.int32); kp = np.ascontiguousarray(n_keep, np.int32)
+    N, A = len(ns), len(st)
+    assert cm.shape == (N, N) and len(cf) == N and len(cb) == N and len(kp) == A
+    s = int(ns.max()) + 1
+    pr = SpSchedProblem(s, N, A, mem_limit, 1 if strict_swap else 0, n_solutions, max_expansions, delta,
+                        *(a.ctypes.data_as(C.c_void_p) for a in (ns, cf, cb, cm, st, kp)))
+    nodes = np.full((A, s), -1, np.int32); stages = np.full((A, s), -1, np.int32); ln = np.zeros(A, np.int32)
+    arrive = np.zeros((A, s), np.float32); e2e = np.zeros(A, np.float32); mx = np.zeros(1, np.float32)
+    _check(lib().sp_schedule_paths(C.byref(pr), _iptr(nodes), _iptr(stages), _iptr(ln), _iptr(arrive), _iptr(e2e),
+                                   _iptr(mx)))
+    return dict(path_nodes=nodes, path_stages=stages, len=ln, arrive=arrive, e2e=e2e, max_e2e=float(mx[0]))
 
 
 # ------------------------------------------------------------------ device context

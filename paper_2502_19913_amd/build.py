@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libskippipe.so")
-SOURCES = ["host.cpp", "engine.hip", "pointwise.hip", "gemm_simple.hip", "gemm_mfma.hip", "attn_simple.hip",
+SOURCES = ["host.cpp", "sched.cpp", "engine.hip", "pointwise.hip", "gemm_simple.hip", "gemm_mfma.hip", "attn_simple.hip",
            "attn_flash.hip", "prof.hip", "optim.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

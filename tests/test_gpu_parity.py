@@ -251,3 +251,17 @@ def test_side_stream_changes_nothing_but_the_order_of_float_additions():
     np.testing.assert_array_equal(a["dx"], b["dx"])
     for k in a["grads"]:
         assert relerr(a["grads"][k], b["grads"][k]) < 1e-5, k
+
+
+def test_scheduled_paths_run_through_the_model():
+    # the host scheduler's stage lists are paths like any other: C1's four stages on 6 emulated nodes
+    cfg = synth.CONFIGS["c1"]
+    node_stage = np.array([0, 0, 1, 2, 3, 3], np.int32)
+    fwd = np.array([1.0, 1.2, 0.9, 1.1, 1.0, 0.8], np.float32)
+    comm = np.full((6, 6), 0.3, np.float32); np.fill_diagonal(comm, 0); comm[0, 2] = comm[2, 0] = 2.5
+    plan = sp.schedule_paths(node_stage, fwd, 2 * fwd, comm, [0, 1], [3, 3], mem_limit=1)
+    paths, lens = plan["path_stages"], plan["len"]
+    named, tok, tgt = inputs(cfg, synth.BASE_SEED)
+    ref = orc.run_paths(cfg, named, paths, lens, tokens=tok, targets=tgt, dtype=np.float64)
+    got = run(cfg, named, paths, lens, tokens=tok, targets=tgt)
+    check_f32(got, ref, "scheduled paths")

@@ -1,0 +1,91 @@
+"""The host path scheduler: its low level against an exhaustive optimum, its output against the constraints
+recomputed independently (CC1-CC3, TC1, TC2), and its error paths.  CPU only."""
+import numpy as np
+import pytest
+
+from paper_2502_19913_amd import binding as sp
+from paper_2502_19913_amd import synth
+from tests import pathcheck
+from tests.schedcheck import check_schedule, single_agent_optimum
+
+
+def world(s, per_stage, seed, first=None):
+    """Nodes in stages (stage 0 may be larger, as Eq. 1 asks), seeded compute and transfer times."""
+    sizes = [first or per_stage] + [per_stage] * (s - 1)
+    node_stage = np.concatenate([[st] * n for st, n in enumerate(sizes)]).astype(np.int32)
+    N = len(node_stage)
+    u = synth.uniform(seed, "sched", N * N + 2 * N).astype(np.float64)
+    fwd = (0.5 + u[:N]).astype(np.float32)
+    bwd = (2.0 * fwd).astype(np.float32)
+    comm = (0.1 + 2.0 * u[2 * N:].reshape(N, N)).astype(np.float32)
+    comm = ((comm + comm.T) / 2).astype(np.float32); np.fill_diagonal(comm, 0)
+    return node_stage, fwd, bwd, comm
+
+
+@pytest.mark.parametrize("s,per,keep,strict", [(4, 2, 3, True), (5, 3, 4, True), (6, 2, 4, False), (4, 3, 4, True),
+                                               (5, 2, 2, True)])
+def test_one_agent_takes_the_exhaustive_optimum(s, per, keep, strict):
+    ns, fwd, bwd, comm = world(s, per, 100 + s + per)
+    res = sp.schedule_paths(ns, fwd, bwd, comm, [0], [keep], mem_limit=8, strict_swap=strict)
+    want = single_agent_optimum(ns, fwd, bwd, comm, 0, keep, strict)
+    assert abs(res["max_e2e"] - want) < 1e-4 * want
+    check_schedule(res, ns, fwd, bwd, comm, [0], [keep], 8, strict)
+
+
+@pytest.mark.parametrize("s,per,first,A,skip,m", [(4, 2, 3, 3, 1, 2), (6, 3, 5, 5, 2, 2), (4, 4, 6, 6, 1, 2),
+                                                  (8, 2, 4, 4, 2, 3), (6, 2, 2, 4, 2, 4), (6, 3, 5, 10, 2, 4)])
+def test_schedule_honours_every_constraint(s, per, first, A, skip, m):
+    ns, fwd, bwd, comm = world(s, per, 7 * s + A, first=first)
+    start = [a % first for a in range(A)]
+    keep = [s - skip] * A
+    res = sp.schedule_paths(ns, fwd, bwd, comm, start, keep, mem_limit=m, delta=0.05)
+    check_schedule(res, ns, fwd, bwd, comm, start, keep, m)
+    # the stage lists are paths the training entry points accept
+    for a in range(A):
+        pathcheck.check_one(res["path_stages"][a, :res["len"][a]], s, strict=True)
+    # no schedule beats the slowest agent's own unconstrained optimum
+    lower = max(single_agent_optimum(ns, fwd, bwd, comm, start[a], keep[a]) for a in range(A))
+    assert res["max_e2e"] >= lower - 1e-4
+
+
+def test_two_agents_on_one_chain_take_turns():
+    # one node per stage, two agents from the same start: the second waits for the first everywhere (TC2)
+    ns = np.array([0, 1, 2], np.int32); fwd = np.array([1, 1, 1], np.float32); bwd = 2 * fwd
+    comm = np.full((3, 3), 0.5, np.float32); np.fill_diagonal(comm, 0)
+    res = sp.schedule_paths(ns, fwd, bwd, comm, [0, 0], [3, 3], mem_limit=2)
+    check_schedule(res, ns, fwd, bwd, comm, [0, 0], [3, 3], 2)
+    alone = single_agent_optimum(ns, fwd, bwd, comm, 0, 3)
+    assert sorted(np.round(res["e2e"], 4)) == [round(alone, 4), round(alone + 1.0, 4)]   # one forward stay later
+
+
+def test_identical_nodes_spread_the_agents():
+    # two nodes per stage, equal costs: two agents from two start nodes need not collide at all
+    ns = np.array([0, 0, 1, 1, 2, 2], np.int32); fwd = np.ones(6, np.float32); bwd = 2 * fwd
+    comm = np.full((6, 6), 0.25, np.float32); np.fill_diagonal(comm, 0)
+    res = sp.schedule_paths(ns, fwd, bwd, comm, [0, 1], [3, 3], mem_limit=1)
+    check_schedule(res, ns, fwd, bwd, comm, [0, 1], [3, 3], 1)
+    assert res["max_e2e"] == pytest.approx(single_agent_optimum(ns, fwd, bwd, comm, 0, 3), rel=1e-5)
+
+
+def test_identical_agents_from_one_start_node_do_not_stay_in_step():
+    # two agents with the same start node and equal latencies collide at time 0; whichever waits, they part
+    ns = np.array([0, 1, 1, 2, 2], np.int32); fwd = np.ones(5, np.float32); bwd = 2 * fwd
+    comm = np.full((5, 5), 0.5, np.float32); np.fill_diagonal(comm, 0)
+    res = sp.schedule_paths(ns, fwd, bwd, comm, [0, 0], [3, 3], mem_limit=2, delta=0.5, max_expansions=100)
+    check_schedule(res, ns, fwd, bwd, comm, [0, 0], [3, 3], 2)
+
+
+def test_rejects_bad_problems():
+    ns = np.array([0, 1, 2], np.int32); one = np.ones(3, np.float32); comm = np.zeros((3, 3), np.float32)
+    with pytest.raises(sp.SpError):
+        sp.schedule_paths(ns, one, one, comm, [1], [3], mem_limit=1)            # start node outside stage 0
+    with pytest.raises(sp.SpError):
+        sp.schedule_paths(ns, one, one, comm, [0], [4], mem_limit=1)            # more stages than exist
+    with pytest.raises(sp.SpError):
+        sp.schedule_paths(np.array([0, 2, 2], np.int32), one, one, comm, [0], [2], mem_limit=1)   # stage 1 has no node
+    with pytest.raises(sp.SpError):
+        sp.schedule_paths(ns, -one, one, comm, [0], [3], mem_limit=1)
+    # three agents, one node per later stage, one path allowed through each node: no solution
+    with pytest.raises(sp.SpError):
+        sp.schedule_paths(np.array([0, 0, 0, 1, 2], np.int32), np.ones(5, np.float32), np.ones(5, np.float32),
+                          np.zeros((5, 5), np.float32), [0, 1, 2], [3, 3, 3], mem_limit=1, max_expansions=200)
