@@ -165,6 +165,61 @@ def eval_mode(args, w, torch, sp, synth):
     print(json.dumps(out))
 
 
+def emulate_mode(args, w, torch, sp, synth):
+    """Scheduler + one stream per emulated node against the same paths on one stream: one JSON line."""
+    import numpy as np
+    from paper_2502_19913_amd.emulate import NodeEmulator
+    cfg = w["cfg"]
+    if not w["whole"]:
+        print("--emulate-nodes needs a whole-model workload (c1 or c2)", file=sys.stderr)
+        sys.exit(2)
+    s, n_mb = cfg["n_stages"], cfg["n_mb"]
+    num, den = cfg["skip"]
+    # node distribution rule: later stages get |S0| (1 - s/(s-1) k) nodes each
+    first = 5 if s >= 6 else 3
+    later = max(1, round(first * (1.0 - s / (s - 1.0) * num / den)))
+    node_stage = np.array([0] * first + [st for st in range(1, s) for _ in range(later)], np.int32)
+    N = len(node_stage)
+    fwd = np.ones(N, np.float32)
+    comm = np.full((N, N), 0.2, np.float32); np.fill_diagonal(comm, 0)
+    keep = [s - (s * num) // den] * n_mb
+    t0 = time.perf_counter()
+    plan = sp.schedule_paths(node_stage, fwd, 2 * fwd, comm, [a % first for a in range(n_mb)], keep,
+                             mem_limit=max(2, n_mb // later + 1), delta=0.05)
+    sched_s = time.perf_counter() - t0
+    em = NodeEmulator(cfg, node_stage, n_mb)
+    run = lambda: em.run(w["params"], w["tok"], w["tgt"], plan["path_nodes"], plan["len"], plan["arrive"], fwd, 2 * fwd, comm)
+    for _ in range(args.warmup):
+        run()
+    walls, busy = [], None
+    for _ in range(args.steps):
+        r = run(); walls.append(r["wall_ms"]); busy = r["busy_ms"]
+    em.close()
+    # the same stage paths on the one stream
+    ctx = w["ctx"]
+    one = lambda: ctx.run_paths(w["params"], w["tok"], w["tgt"], plan["path_stages"], plan["len"], w["grads"])
+    for _ in range(args.warmup):
+        one()
+    torch.cuda.synchronize(); t0 = time.perf_counter()
+    for _ in range(args.steps):
+        loss, _ = one()
+    torch.cuda.synchronize(); single_ms = (time.perf_counter() - t0) / args.steps * 1e3
+    wall = float(np.median(walls)); Nmb = cfg["seqs_per_mb"] * cfg["seq_len"]
+    out = {"metric": "tokens/sec of one iteration over emulated pipeline nodes (one stream per node) on 1 MI355X",
+           "value": round(n_mb * Nmb / wall * 1e3, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": round(wall, 3), "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "bf16" if cfg["dtype"] == "bf16" else "f32",
+           "data": "synthetic (seeded): N(0,0.02) weights, uniform tokens; unit node times, 0.2 per transfer",
+           "config": {"workload": f"{args.config} whole model over {N} emulated nodes (stage sizes {first}+{later}x{s - 1}), "
+                                  f"{n_mb} microbatches scheduled by sp_schedule_paths", "id": args.config,
+                      "n_mb": n_mb, "tokens_per_mb": Nmb, "nodes": N},
+           "ms_per_step_one_stream_grouped": round(single_ms, 3), "scheduler_seconds": round(sched_s, 4),
+           "planned_max_latency": round(plan["max_e2e"], 3),
+           "node_busy_fraction": [round(b / wall, 3) for b in busy], "loss": round(loss, 4)}
+    ctx.close()
+    print(json.dumps(out))
+
+
 def cpu_baseline(key, synth):
     """The CPU checker timed on a bounded sample of the same workload (float32 instantiation)."""
     import numpy as np
@@ -222,6 +277,9 @@ def main():
     ap.add_argument("--serial", action="store_true",
                     help="keep the weight-gradient products in line on the one stream (no side stream) for the "
                          "whole run; by default only the per-launch timing pass runs that way")
+    ap.add_argument("--emulate-nodes", action="store_true",
+                    help="whole-model workloads (c1, c2): schedule the microbatches over emulated nodes (stage sizes "
+                         "by the paper's node-distribution rule) and run them one stream per node")
     ap.add_argument("--one-group", action="store_true",
                     help="stage-share workloads: all routed microbatches as one group (upper bound of the rate)")
     args = ap.parse_args()
@@ -238,6 +296,8 @@ def main():
     w = build_workload(args.config, torch, sp, synth)
     if args.eval_skip:
         return eval_mode(args, w, torch, sp, synth)
+    if args.emulate_nodes:
+        return emulate_mode(args, w, torch, sp, synth)
     if args.one_group and not w["whole"]:
         mbs = sorted(m for _, _, g in w["plan"] for m in g)
         w["plan"] = [(w["plan"][0][0], w["stage"], mbs)]

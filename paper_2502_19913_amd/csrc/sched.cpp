@@ -258,9 +258,22 @@ extern "C" int sp_schedule_paths(const sp_sched_problem* q, int32_t* path_nodes,
     order = by_speed(*T, order);
     std::vector<char> shielded(P.A, 0);
     for (int i = 0; i < protect; ++i) shielded[order[P.A - 1 - i]] = 1;
+    // among equally fast paths, the agents that have been turned away from the fewest nodes so far go first:
+    // with equal nodes everywhere the fastest-first rule alone would keep picking the same agents until they
+    // have no stage left
+    auto barred = [&](int a) {
+      int n = 0;
+      for (const Constraint& c : T->cons[a]) n += c.t1 == kInf && c.t0 == -kInf;
+      return n;
+    };
+    std::vector<int> sorted = by_speed(*T, through);
+    std::stable_sort(sorted.begin(), sorted.end(), [&](int x, int y) {
+      if (std::fabs(T->paths[x].e2e - T->paths[y].e2e) > 1e-9) return false;   // keep the speed order
+      return barred(x) < barred(y);
+    });
     std::vector<int> cand;
-    for (int a : by_speed(*T, through)) if (!shielded[a]) cand.push_back(a);
-    for (int a : by_speed(*T, through)) if (shielded[a]) cand.push_back(a);
+    for (int a : sorted) if (!shielded[a]) cand.push_back(a);
+    for (int a : sorted) if (shielded[a]) cand.push_back(a);
     for (int shift = 0; shift < 3 && shift + excess <= (int)cand.size(); ++shift) {
       std::vector<int> pick(cand.begin() + shift, cand.begin() + shift + excess);
       Solution* S = make(T);
