@@ -136,7 +136,6 @@ __global__ __launch_bounds__(kBlock) void k_rmsnorm_bwd(const T* __restrict__ dy
   extern __shared__ float s_dg[];
   const int lane = threadIdx.x & 63;
   const int64_t nw = (int64_t)gridDim.x * kWavesPerBlock;
-  for (int c = threadIdx.x; c < d; c += kBlock) s_dg[c] = 0.f;
   float acc[NV][8];
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
@@ -182,17 +181,24 @@ __global__ __launch_bounds__(kBlock) void k_rmsnorm_bwd(const T* __restrict__ dy
       }
     }
   }
-  __syncthreads();
+  // fold the block's four wavefronts: each writes its partial sums to its own row of LDS, then every column is
+  // added up by one thread and goes out as one atomic
+  float* part = s_dg + (size_t)(threadIdx.x >> 6) * d;
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
     int col = (lane + 64 * i) * 8;
     if (col < d) {
 #pragma unroll
-      for (int j = 0; j < 8; ++j) atomicAdd(&s_dg[col + j], acc[i][j]);
+      for (int j = 0; j < 8; ++j) part[col + j] = acc[i][j];
     }
   }
   __syncthreads();
-  for (int c = threadIdx.x; c < d; c += kBlock) unsafeAtomicAdd(dg + c, s_dg[c]);
+  for (int c = threadIdx.x; c < d; c += kBlock) {
+    float v = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWavesPerBlock; ++w) v += s_dg[(size_t)w * d + c];
+    unsafeAtomicAdd(dg + c, v);
+  }
 }
 
 template <class T>
@@ -469,15 +475,16 @@ template <class T>
 static void rmsnorm_bwd_t(hipStream_t s, const T* dy, const T* x, const T* g, const float* rstd, const T* dres,
                           int64_t R, int d, T* dx, float* dg) {
   if (R <= 0) return;
-  bool vec = d % 8 == 0 && d <= 8192 && aligned16<T>(x) && aligned16<T>(g) && aligned16<T>(dy) && aligned16<T>(dx) &&
+  // the gain-gradient fold keeps one row of d floats per wavefront in LDS: 64 KB at d = 4096
+  bool vec = d % 8 == 0 && d <= 4096 && aligned16<T>(x) && aligned16<T>(g) && aligned16<T>(dy) && aligned16<T>(dx) &&
              (!dres || aligned16<T>(dres));
   if (!vec) {
     int grid = grid_for_rows(R, kWavesPerBlock, 16384);
     hipLaunchKernelGGL(k_rmsnorm_bwd_scalar<T>, dim3(grid), dim3(kBlock), 0, s, dy, x, g, rstd, dres, R, d, dx, dg);
     return;
   }
-  int grid = grid_for_rows(R, kWavesPerBlock * 8, 1024);  // >= 8 rows per wavefront amortises the dg fold
-  size_t lds = (size_t)d * sizeof(float);
+  int grid = grid_for_rows(R, kWavesPerBlock * 4, 1024);  // >= 4 rows per wavefront amortise the dg fold
+  size_t lds = (size_t)d * sizeof(float) * kWavesPerBlock;
   int nv = (d + 511) / 512;
 #define SP_CASE(N) hipLaunchKernelGGL((k_rmsnorm_bwd<T, N>), dim3(grid), dim3(kBlock), lds, s, dy, x, g, rstd, dres, R, d, dx, dg)
   if (nv <= 1) SP_CASE(1); else if (nv <= 2) SP_CASE(2); else if (nv <= 4) SP_CASE(4); else if (nv <= 8) SP_CASE(8); else SP_CASE(16);
