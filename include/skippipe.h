@@ -155,6 +155,8 @@ typedef struct sp_sched_problem {
   int32_t strict_swap; /* CC2: exchanged stages must be consecutive */
   int32_t n_solutions, max_expansions;
   float delta;
+  float focal_slack;   /* second phase: among solutions within this fraction of the cheapest, the one with the
+                          fewest collisions is expanded next; 0 = strictly cheapest first (the paper); < 0 = 0.5 */
   const int32_t* node_stage;
   const float* compute_fwd;
   const float* compute_bwd;

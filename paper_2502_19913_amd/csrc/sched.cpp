@@ -157,6 +157,7 @@ struct Solution {
   std::vector<std::vector<Constraint>> cons;   // per agent
   std::vector<AgentPath> paths;
   double cost = 0;
+  int collisions = 0;   // pairs of forward stays that overlap on a node
   void recost() { cost = 0; for (const AgentPath& p : paths) cost = std::max(cost, p.e2e); }
 };
 struct ByCost {
@@ -175,12 +176,53 @@ std::vector<int> by_speed(const Solution& T, const std::vector<int>& agents) {
   return v;
 }
 
+int count_collisions(const Problem& P, const Solution& S) {
+  int n = 0;
+  for (int x = 0; x < P.A; ++x)
+    for (int y = x + 1; y < P.A; ++y) {
+      const AgentPath &pi = S.paths[x], &pj = S.paths[y];
+      for (size_t u = 0; u < pi.nodes.size(); ++u)
+        for (size_t v = 0; v < pj.nodes.size(); ++v)
+          if (pi.nodes[u] == pj.nodes[v]) {
+            const double a0 = pi.arrive[u], a1 = a0 + P.fwd[pi.nodes[u]], b0 = pj.arrive[v], b1 = b0 + P.fwd[pj.nodes[v]];
+            n += a0 < b1 - 1e-9 && b0 < a1 - 1e-9;
+          }
+    }
+  return n;
+}
+
 bool replan(const Problem& P, Solution* S, const std::vector<int>& agents) {
   for (int a : agents)
     if (!plan_agent(P, a, S->cons[a], &S->paths[a])) return false;
   S->recost();
+  S->collisions = count_collisions(P, *S);
   return true;
 }
+
+// Open list of the second phase: the paper takes the cheapest solution next; among the solutions within
+// `slack` of the cheapest this one takes the one with the fewest collisions left (a focal search), which
+// reaches a collision-free schedule in far fewer expansions when many agents share few nodes.
+struct Focal {
+  std::vector<Solution*> v;
+  double slack;
+  bool empty() const { return v.empty(); }
+  void push(Solution* s) { v.push_back(s); }
+  Solution* pop() {
+    double best = kInf;
+    for (Solution* s : v) best = std::min(best, s->cost);
+    size_t pick = 0;
+    bool have = false;
+    for (size_t i = 0; i < v.size(); ++i) {
+      if (v[i]->cost > best * (1.0 + slack) + 1e-12) continue;
+      if (!have || v[i]->collisions < v[pick]->collisions ||
+          (v[i]->collisions == v[pick]->collisions && v[i]->cost < v[pick]->cost)) { pick = i; have = true; }
+    }
+    Solution* s = v[pick];
+    v[pick] = v.back();
+    v.pop_back();
+    return s;
+  }
+};
 
 }  // namespace
 }  // namespace sp
@@ -235,14 +277,14 @@ extern "C" int sp_schedule_paths(const sp_sched_problem* q, int32_t* path_nodes,
     for (int a = 0; a < P.A; ++a) everyone[a] = a;
     if (!replan(P, root, everyone)) { cleanup(); return fail(SP_EPATH, "schedule: an agent has no path at all"); }
   }
-  std::priority_queue<Solution*, std::vector<Solution*>, ByCost> open, done;
+  std::priority_queue<Solution*, std::vector<Solution*>, ByCost> open;
+  Focal done{{}, q->focal_slack >= 0.f ? (double)q->focal_slack : 0.5};
   open.push(root);
   // CC3 on solution T: false if it holds; else pushes children into `into`, each with the over-visited stage
   // forbidden to `excess` of the paths through it: first the fastest ones (the paper's choice; never the
   // slowest quarter of the agents unless nobody else is left), then the same window moved on by one and by
   // two paths, so that a choice that leaves some agent without a path is not the end of the search
-  typedef std::priority_queue<Solution*, std::vector<Solution*>, ByCost> Heap;
-  auto resolve_cc3 = [&](Solution* T, Heap* into) -> bool {
+  auto resolve_cc3 = [&](Solution* T, auto* into) -> bool {
     int bad = -1;
     std::vector<int> through;
     for (int st = 1; st < P.s && bad < 0; ++st) {
@@ -271,9 +313,23 @@ extern "C" int sp_schedule_paths(const sp_sched_problem* q, int32_t* path_nodes,
       if (std::fabs(T->paths[x].e2e - T->paths[y].e2e) > 1e-9) return false;   // keep the speed order
       return barred(x) < barred(y);
     });
+    // an agent that already has as many stages barred as it leaves out cannot give up another one
+    auto can_give_up = [&](int a) {
+      int barred_stages = 0;
+      for (int st = 1; st < P.s; ++st) {
+        bool all = true;
+        for (int nd : P.stage_nodes[st]) {
+          bool found = false;
+          for (const Constraint& c : T->cons[a]) found = found || (c.node == nd && c.t0 == -kInf && c.t1 == kInf);
+          all = all && found;
+        }
+        barred_stages += all;
+      }
+      return barred_stages < P.s - P.keep[a];
+    };
     std::vector<int> cand;
-    for (int a : sorted) if (!shielded[a]) cand.push_back(a);
-    for (int a : sorted) if (shielded[a]) cand.push_back(a);
+    for (int a : sorted) if (!shielded[a] && can_give_up(a)) cand.push_back(a);
+    for (int a : sorted) if (shielded[a] && can_give_up(a)) cand.push_back(a);
     for (int shift = 0; shift < 3 && shift + excess <= (int)cand.size(); ++shift) {
       std::vector<int> pick(cand.begin() + shift, cand.begin() + shift + excess);
       Solution* S = make(T);
@@ -295,8 +351,7 @@ extern "C" int sp_schedule_paths(const sp_sched_problem* q, int32_t* path_nodes,
   int rc = SP_EPATH;
   const Solution* found = nullptr;
   while (!done.empty() && expansions < max_expansions) {
-    Solution* T = done.top();
-    done.pop();
+    Solution* T = done.pop();
     if (resolve_cc3(T, &done)) continue;
     // TC1: at most m paths through a node
     int over = -1;
@@ -358,8 +413,9 @@ extern "C" int sp_schedule_paths(const sp_sched_problem* q, int32_t* path_nodes,
   }
   if (rc != SP_OK) {
     cleanup();
-    return fail(SP_EPATH, expansions >= max_expansions ? "schedule: expansion limit reached without a conflict-free solution"
-                                                       : "schedule: no conflict-free solution");
+    return fail(SP_EPATH, std::string(expansions >= max_expansions ? "schedule: expansion limit reached" : "schedule: search exhausted") +
+                              " without a conflict-free solution (" + std::to_string(collected) +
+                              " solutions passed the first phase, " + std::to_string(expansions) + " expansions)");
   }
   double worst = 0;
   for (int a = 0; a < P.A; ++a) {

@@ -33,7 +33,8 @@ def test_one_agent_takes_the_exhaustive_optimum(s, per, keep, strict):
 
 
 @pytest.mark.parametrize("s,per,first,A,skip,m", [(4, 2, 3, 3, 1, 2), (6, 3, 5, 5, 2, 2), (4, 4, 6, 6, 1, 2),
-                                                  (8, 2, 4, 4, 2, 3), (6, 2, 2, 4, 2, 4), (6, 3, 5, 10, 2, 4)])
+                                                  (8, 2, 4, 4, 2, 3), (6, 2, 2, 4, 2, 4), (6, 3, 5, 10, 2, 4),
+                                                  (6, 3, 5, 20, 2, 12), (8, 4, 6, 24, 2, 12)])
 def test_schedule_honours_every_constraint(s, per, first, A, skip, m):
     ns, fwd, bwd, comm = world(s, per, 7 * s + A, first=first)
     start = [a % first for a in range(A)]
@@ -89,3 +90,14 @@ def test_rejects_bad_problems():
     with pytest.raises(sp.SpError):
         sp.schedule_paths(np.array([0, 0, 0, 1, 2], np.int32), np.ones(5, np.float32), np.ones(5, np.float32),
                           np.zeros((5, 5), np.float32), [0, 1, 2], [3, 3, 3], mem_limit=1, max_expansions=200)
+
+
+def test_cheapest_first_and_focal_orders_agree_where_both_finish():
+    # focal_slack 0 is the paper's order (cheapest solution next); a wider focus may only cost latency
+    ns, fwd, bwd, comm = world(6, 3, 41, first=5)
+    start = [a % 5 for a in range(8)]; keep = [4] * 8
+    strict = sp.schedule_paths(ns, fwd, bwd, comm, start, keep, mem_limit=4, delta=0.05, focal_slack=0.0)
+    focal = sp.schedule_paths(ns, fwd, bwd, comm, start, keep, mem_limit=4, delta=0.05, focal_slack=0.5)
+    check_schedule(strict, ns, fwd, bwd, comm, start, keep, 4)
+    check_schedule(focal, ns, fwd, bwd, comm, start, keep, 4)
+    assert focal["max_e2e"] <= 1.5 * strict["max_e2e"] + 1e-4
