@@ -153,6 +153,7 @@ typedef struct sp_sched_problem {
   int32_t n_stages, n_nodes, n_agents;
   int32_t mem_limit;   /* m of TC1 */
   int32_t strict_swap; /* CC2: exchanged stages must be consecutive */
+  int32_t no_swap;     /* != 0: stages strictly in increasing order (no exchange at all) */
   int32_t n_solutions, max_expansions;
   float delta;
   float focal_slack;   /* second phase: among solutions within this fraction of the cheapest, the one with the

@@ -159,13 +159,13 @@ def unpack(cfg: dict, flat) -> Dict[str, np.ndarray]:
 
 
 class SpSchedProblem(C.Structure):
-    _fields_ = [(n, C.c_int32) for n in ("n_stages", "n_nodes", "n_agents", "mem_limit", "strict_swap", "n_solutions",
+    _fields_ = [(n, C.c_int32) for n in ("n_stages", "n_nodes", "n_agents", "mem_limit", "strict_swap", "no_swap", "n_solutions",
                                          "max_expansions")] + [("delta", C.c_float), ("focal_slack", C.c_float)] + \
                [(n, C.c_void_p) for n in ("node_stage", "compute_fwd", "compute_bwd", "comm", "start_node", "n_keep")]
 
 
 def schedule_paths(node_stage, compute_fwd, compute_bwd, comm, start_node, n_keep, mem_limit, strict_swap=True,
-                   n_solutions=32, max_expansions=20000, delta=0.0, focal_slack=-1.0) -> dict:
+                   n_solutions=32, max_expansions=20000, delta=0.0, focal_slack=-1.0, allow_swap=True) -> dict:
     """Path scheduler (host only): returns path_nodes, path_stages [A][s] (-1 padded), len, arrive, e2e, max_e2e."""
     ns = np.ascontiguousarray(node_stage, np.int32)
     cf = np.ascontiguousarray(compute_fwd, np.float32); cb = np.ascontiguousarray(compute_bwd, np.float32)
@@ -174,7 +174,8 @@ def schedule_paths(node_stage, compute_fwd, compute_bwd, comm, start_node, n_kee
     N, A = len(ns), len(st)
     assert cm.shape == (N, N) and len(cf) == N and len(cb) == N and len(kp) == A
     s = int(ns.max()) + 1
-    pr = SpSchedProblem(s, N, A, mem_limit, 1 if strict_swap else 0, n_solutions, max_expansions, delta, focal_slack,
+    pr = SpSchedProblem(s, N, A, mem_limit, 1 if strict_swap else 0, 0 if allow_swap else 1, n_solutions, max_expansions,
+                        delta, focal_slack,
                         *(a.ctypes.data_as(C.c_void_p) for a in (ns, cf, cb, cm, st, kp)))
     nodes = np.full((A, s), -1, np.int32); stages = np.full((A, s), -1, np.int32); ln = np.zeros(A, np.int32)
     arrive = np.zeros((A, s), np.float32); e2e = np.zeros(A, np.float32); mx = np.zeros(1, np.float32)

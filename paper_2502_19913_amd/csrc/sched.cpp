@@ -53,7 +53,7 @@ struct AgentPath {
 };
 
 struct Problem {
-  int s, N, A, m, strict;
+  int s, N, A, m, strict, no_swap;
   const int32_t* node_stage;
   const float *fwd, *bwd, *comm;
   const int32_t *start, *keep;
@@ -122,7 +122,7 @@ bool plan_agent(const Problem& P, int a, const std::vector<Constraint>& cs, Agen
       if (st < mx) {
         // the second half of the one exchange (CC2): straight after the largest stage so far, a stage between
         // it and the next largest (in the strict form: the stage just below it); stage 0 is never exchanged
-        if (cur.swap || last != mx || st <= second || count < 2 || (P.strict && mx - st != 1)) continue;
+        if (P.no_swap || cur.swap || last != mx || st <= second || count < 2 || (P.strict && mx - st != 1)) continue;
         swap = 1;
       }
       for (int nd : P.stage_nodes[st]) {
@@ -236,7 +236,7 @@ extern "C" int sp_schedule_paths(const sp_sched_problem* q, int32_t* path_nodes,
       !q->node_stage || !q->compute_fwd || !q->compute_bwd || !q->comm || !q->start_node || !q->n_keep)
     return fail(SP_EINVAL, "schedule: bad sizes or null arrays");
   Problem P;
-  P.s = q->n_stages; P.N = q->n_nodes; P.A = q->n_agents; P.m = q->mem_limit; P.strict = q->strict_swap;
+  P.s = q->n_stages; P.N = q->n_nodes; P.A = q->n_agents; P.m = q->mem_limit; P.strict = q->strict_swap; P.no_swap = q->no_swap;
   P.node_stage = q->node_stage; P.fwd = q->compute_fwd; P.bwd = q->compute_bwd; P.comm = q->comm;
   P.start = q->start_node; P.keep = q->n_keep;
   P.stage_nodes.assign(P.s, {});

@@ -1,5 +1,7 @@
 """The host path scheduler: its low level against an exhaustive optimum, its output against the constraints
 recomputed independently (CC1-CC3, TC1, TC2), and its error paths.  CPU only."""
+import os
+
 import numpy as np
 import pytest
 
@@ -57,6 +59,31 @@ def test_two_agents_on_one_chain_take_turns():
     check_schedule(res, ns, fwd, bwd, comm, [0, 0], [3, 3], 2)
     alone = single_agent_optimum(ns, fwd, bwd, comm, 0, 3)
     assert sorted(np.round(res["e2e"], 4)) == [round(alone, 4), round(alone + 1.0, 4)]   # one forward stay later
+
+
+def test_worked_chain_example_of_the_paper():
+    # appendix "Path Coarsening": A-B-C with 1, 2, 1 seconds per microbatch and 1 second per transfer; two
+    # microbatches keep A busy for 2 s, B for 4 s, and leave C idle for 1 s between them
+    rows = [l.split() for l in open(os.path.join(os.path.dirname(__file__), "golden", "abc_chain_example.txt"))
+            if l.strip() and not l.startswith("#")]
+    fwd = np.array([float(r[1]) for r in rows[:3]], np.float32)
+    tr, n_mb, busy_a, busy_b, gap_c = (float(x) for x in rows[3])
+    ns = np.array([0, 1, 2], np.int32)
+    comm = np.full((3, 3), tr, np.float32); np.fill_diagonal(comm, 0)
+    res = sp.schedule_paths(ns, fwd, fwd, comm, [0] * int(n_mb), [3] * int(n_mb), mem_limit=int(n_mb), allow_swap=False)
+    check_schedule(res, ns, fwd, fwd, comm, [0] * int(n_mb), [3] * int(n_mb), int(n_mb))
+    stays = {n: sorted((float(res["arrive"][a, n]), float(res["arrive"][a, n]) + float(fwd[n])) for a in range(int(n_mb)))
+             for n in range(3)}
+    assert stays[0][-1][1] - stays[0][0][0] == pytest.approx(busy_a)        # back to back on A
+    assert stays[1][-1][1] - stays[1][0][0] == pytest.approx(busy_b)        # back to back on B
+    assert stays[1][1][0] == pytest.approx(stays[1][0][1])
+    assert stays[2][1][0] - stays[2][0][1] == pytest.approx(gap_c)          # C waits for B
+    # with the one exchange CC2 allows, the second microbatch visits C before B and nobody waits: the slowest
+    # microbatch finishes earlier than in the in-order schedule
+    swapped = sp.schedule_paths(ns, fwd, fwd, comm, [0] * int(n_mb), [3] * int(n_mb), mem_limit=int(n_mb))
+    check_schedule(swapped, ns, fwd, fwd, comm, [0] * int(n_mb), [3] * int(n_mb), int(n_mb))
+    assert sorted(map(tuple, swapped["path_stages"].tolist())) == [(0, 1, 2), (0, 2, 1)]
+    assert swapped["max_e2e"] < res["max_e2e"]
 
 
 def test_identical_nodes_spread_the_agents():
