@@ -175,10 +175,10 @@ def emulate_mode(args, w, torch, sp, synth):
         sys.exit(2)
     s, n_mb = cfg["n_stages"], cfg["n_mb"]
     num, den = cfg["skip"]
-    # node distribution rule: later stages get |S0| (1 - s/(s-1) k) nodes each
-    first = 5 if s >= 6 else 3
-    later = max(1, round(first * (1.0 - s / (s - 1.0) * num / den)))
-    node_stage = np.array([0] * first + [st for st in range(1, s) for _ in range(later)], np.int32)
+    # node distribution rule (Eq. 1) over the paper's node counts: 20 nodes for six stages, 18 for four
+    sizes = sp.stage_sizes(20 if s >= 6 else (18 if s >= 4 else 3 * s), s, num, den)
+    first, later = sizes[0], sizes[1] if s > 1 else 0
+    node_stage = np.array([st for st, n in enumerate(sizes) for _ in range(n)], np.int32)
     N = len(node_stage)
     fwd = np.ones(N, np.float32)
     comm = np.full((N, N), 0.2, np.float32); np.fill_diagonal(comm, 0)

@@ -149,6 +149,12 @@ int sp_route_plan(const sp_cfg* cfg, const int32_t* paths, const int32_t* len, i
  * may be null); e2e [n_agents] and max_e2e (may be null).  SP_EPATH: no conflict-free solution found within
  * max_expansions (20000 if <= 0) constraint-tree expansions; SP_EINVAL: bad sizes, a start node outside
  * stage 0, a stage without nodes, negative times. */
+/* Nodes per stage by the node distribution rule (section "Allocating Nodes to Stages", Eq. 1): later stages
+ * see only a share 1 - s/(s-1) k of the microbatches, so |S_i| = |S_0| (1 - s/(s-1) k) for i >= 1.  sizes: host
+ * int32 [n_stages]; every node is used; the later stages get the nearest whole number, stage 0 the rest.
+ * SP_EINVAL if fewer nodes than stages or the ratio leaves the later stages nothing. */
+int sp_stage_sizes(int n_nodes, int n_stages, int skip_num, int skip_den, int32_t* sizes);
+
 typedef struct sp_sched_problem {
   int32_t n_stages, n_nodes, n_agents;
   int32_t mem_limit;   /* m of TC1 */

@@ -20,7 +20,7 @@ SP_F32, SP_BF16 = 0, 1
 SP_STRICT_CC, SP_SWAP_ANY_GAP, SP_ALLOW_ANY_ORDER = 0, 1, 2
 
 EXPORTS = ["sp_param_count", "sp_param_layout", "sp_workspace_bytes", "sp_make_paths", "sp_check_paths",
-           "sp_route_plan", "sp_schedule_paths", "sp_strerror", "sp_create", "sp_destroy", "sp_reset", "sp_set_side_stream", "sp_embed_fwd", "sp_embed_bwd",
+           "sp_route_plan", "sp_schedule_paths", "sp_stage_sizes", "sp_strerror", "sp_create", "sp_destroy", "sp_reset", "sp_set_side_stream", "sp_embed_fwd", "sp_embed_bwd",
            "sp_stage_fwd", "sp_stage_bwd", "sp_head_fwd_bwd", "sp_run_paths", "sp_eval_paths", "sp_gemm", "sp_attention_fwd",
            "sp_attention_bwd", "sp_optim_workspace_bytes", "sp_optim_step", "sp_prof_begin", "sp_prof_end"]
 
@@ -162,6 +162,12 @@ class SpSchedProblem(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_stages", "n_nodes", "n_agents", "mem_limit", "strict_swap", "no_swap", "n_solutions",
                                          "max_expansions")] + [("delta", C.c_float), ("focal_slack", C.c_float)] + \
                [(n, C.c_void_p) for n in ("node_stage", "compute_fwd", "compute_bwd", "comm", "start_node", "n_keep")]
+
+
+def stage_sizes(n_nodes: int, n_stages: int, skip_num: int, skip_den: int) -> List[int]:
+    out = np.zeros(n_stages, np.int32)
+    _check(lib().sp_stage_sizes(C.c_int(n_nodes), C.c_int(n_stages), C.c_int(skip_num), C.c_int(skip_den), _iptr(out)))
+    return [int(x) for x in out]
 
 
 def schedule_paths(node_stage, compute_fwd, compute_bwd, comm, start_node, n_keep, mem_limit, strict_swap=True,

@@ -229,6 +229,23 @@ struct Focal {
 
 using namespace sp;
 
+// Eq. 1 of "Allocating Nodes to Stages": |S_i| = |S_0| (1 - s/(s-1) k) for i >= 1, with all n_nodes used.
+extern "C" int sp_stage_sizes(int n_nodes, int n_stages, int skip_num, int skip_den, int32_t* sizes) {
+  if (!sizes || n_stages < 1 || n_nodes < n_stages || skip_den <= 0 || skip_num < 0)
+    return fail(SP_EINVAL, "stage_sizes: bad arguments");
+  if (n_stages == 1) { sizes[0] = n_nodes; return SP_OK; }
+  const double s = n_stages, k = (double)skip_num / skip_den;
+  const double r = 1.0 - s / (s - 1.0) * k;   // |S_i| / |S_0|
+  if (!(r > 0.0)) return fail(SP_EINVAL, "stage_sizes: the skip ratio leaves the later stages no node");
+  const double first = n_nodes / (1.0 + (s - 1.0) * r);
+  // nearest whole numbers that use every node: later stages get round(first * r), stage 0 the rest
+  int later = (int)std::lround(first * r);
+  later = std::max(1, std::min(later, (n_nodes - 1) / (n_stages - 1)));
+  sizes[0] = n_nodes - later * (n_stages - 1);
+  for (int i = 1; i < n_stages; ++i) sizes[i] = later;
+  return SP_OK;
+}
+
 extern "C" int sp_schedule_paths(const sp_sched_problem* q, int32_t* path_nodes, int32_t* path_stages, int32_t* len,
                                  float* arrive, float* e2e, float* max_e2e) {
   if (!q || !path_nodes || !path_stages || !len) return fail(SP_EINVAL, "schedule: null argument");

@@ -128,3 +128,18 @@ def test_cheapest_first_and_focal_orders_agree_where_both_finish():
     check_schedule(strict, ns, fwd, bwd, comm, start, keep, 4)
     check_schedule(focal, ns, fwd, bwd, comm, start, keep, 4)
     assert focal["max_e2e"] <= 1.5 * strict["max_e2e"] + 1e-4
+
+
+def test_stage_sizes_reproduce_the_papers_set_ups():
+    # appendix "Test Configurations": 18 nodes / 4 stages / 25 % -> (6,4,4,4); 20 nodes / 6 stages / 33 % -> (5,3,3,3,3,3)
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "eq1_stage_sizes.txt")):
+        if not line.strip() or line.startswith("#"):
+            continue
+        s, num, den, n0, ni = (int(x) for x in line.split())
+        assert sp.stage_sizes(n0 + ni * (s - 1), s, num, den) == [n0] + [ni] * (s - 1)
+    assert sp.stage_sizes(7, 1, 0, 1) == [7]
+    assert sum(sp.stage_sizes(23, 6, 1, 3)) == 23                      # every node is used
+    with pytest.raises(sp.SpError):
+        sp.stage_sizes(3, 4, 1, 4)
+    with pytest.raises(sp.SpError):
+        sp.stage_sizes(10, 2, 1, 2)                                    # 1 - 2 * 1/2 = 0: nothing left for stage 1
