@@ -147,3 +147,22 @@ def test_workspace_bytes_grows_with_visits():
     d, h, T = 2048, 5632, 4096
     est = 4 * T * ((6 * d + 2 * d + 3 * h) * 2 + 16 * 4 + 8)
     assert 0.98 * est < per_visit < 1.05 * est
+
+
+def test_product_path_refuses_to_run_without_a_gpu():
+    # there is no CPU fallback: a context cannot be made where no HIP device is present
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(RuntimeError):
+        sp.Context(synth.CONFIGS["c1"], 1, 1)
+    # and nothing in the product imports the CPU checker
+    import os, re
+    pkg = os.path.join(ROOT, "paper_2502_19913_amd")
+    for dirpath, _, files in os.walk(pkg):
+        if "_build" in dirpath:
+            continue
+        for f in files:
+            if f.endswith((".py", ".hip", ".cpp", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"^\s*(from|import)\s+oracle|#include\s+\".*oracle", text, re.M), (dirpath, f)
