@@ -2,11 +2,11 @@
 // v_mfma_f32_16x16x32_bf16, which on random data sustains more flops per watt than the 32x32x16 form (the chip
 // is power-limited here); op 2 keeps v_mfma_f32_32x32x16_bf16, whose accumulator layout gives wider atomics.
 //
-// One workgroup of 8 wavefronts owns a 256x256 tile of the output and walks the reduction
-// dimension in steps of 64.  Operand tiles go from memory straight into LDS (buffer loads with the LDS
-// modifier: no staging registers, no LDS stores; the hardware range check returns zero past the end
-// of an operand, so ragged edges need no branches), one step ahead of the MFMAs, into two stages of
-// 64 KB; one barrier per step.
+// One workgroup of 8 wavefronts owns a 256x256 tile of the output (128x128 when the product has too few
+// 256-tiles to occupy the CUs) and walks the reduction dimension in steps of 64.  Operand tiles go from
+// memory straight into LDS (buffer loads with the LDS modifier: no staging registers, no LDS stores; the
+// hardware range check returns zero past the end of an operand, so ragged edges need no branches), one
+// step ahead of the MFMAs, into two stages (64 KB each for the large tile); one barrier per step.
 //
 // LDS layouts.  A load instruction fills 1 KiB of LDS in lane order, so tiles are unpadded and the
 // 16-byte chunks of a row are permuted by an XOR with bits of the row number (see Operand), which
@@ -45,13 +45,19 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) int i32x4;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 
-constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int BK = 64;
 constexpr int kThreads = 512;
-constexpr int kTileBytes = 256 * BK * 2;        // one operand tile, either layout, unpadded
-constexpr int kStageBytes = 2 * kTileBytes;     // A and B
-constexpr int kCRowBytes = 528;                 // output staging: 256 bf16 + 16 bytes
-constexpr int kLdsBytes = 256 * kCRowBytes;     // >= two stages
-static_assert(2 * kStageBytes <= kLdsBytes, "two stages fit under the output staging");
+// Geometry of a TILE x TILE output tile (TILE = 256, or 128 for products with few tiles)
+template <int TILE>
+struct Geo {
+  static constexpr int kTileBytes = TILE * BK * 2;        // one operand tile, either layout, unpadded
+  static constexpr int kStageBytes = 2 * kTileBytes;      // A and B
+  static constexpr int kCRowBytes = TILE * 2 + 16;        // output staging row: TILE bf16 + 16 bytes
+  static constexpr int kLdsBytes = TILE * kCRowBytes > 2 * kStageBytes ? TILE * kCRowBytes : 2 * kStageBytes;
+  static constexpr int NJ = kTileBytes / 1024 / 8;        // load instructions per wavefront and operand tile
+  static constexpr int XCH = TILE / 8;                    // 16-byte chunks per k row of a k-strided tile
+  static constexpr int WM = TILE / 2, WN = TILE / 4;      // a wavefront's share of the tile (2 x 4 wavefronts)
+};
 
 // Buffer loads with the LDS modifier, written as assembly so that the compiler's wait insertion does not
 // see them (it would make the first LDS read after each of them wait for it).  One instruction copies
@@ -68,21 +74,22 @@ __device__ __forceinline__ void load_to_lds16(u32x4 desc, lds_ptr lds, uint32_t 
 }
 constexpr uint32_t kPastEnd = 0x80000000u;      // no descriptor is this large
 
-// One operand's share of the tile loads for one wavefront: 4 instructions of 1 KiB per step.
+// One operand's share of the tile loads for one wavefront: TILE / 64 instructions of 1 KiB per step.
 // Instruction j fills the tile's 16-byte chunks (8j + wave) * 64 + lane.
-//   k-contiguous tile: [256 rows][64 k], 8 chunks per row; the chunk at position p of a row holds the row's
+//   k-contiguous tile: [TILE rows][64 k], 8 chunks per row; the chunk at position p of a row holds the row's
 //     chunk p ^ ((row >> 1) & 7): the 16 rows a ds_read_b128 touches then fall in 16 different bank groups.
-//   k-strided tile: [64 k][256 x], 32 chunks per k row; position p of k row k holds chunk p ^ kkey(k).
+//   k-strided tile: [64 k][TILE x], TILE / 8 chunks per k row; position p of k row k holds chunk p ^ kkey(k).
 //     For 16-wide fragments kkey(k) = ((k & 3) | ((k >> 3) & 1) << 2) << 1: the 8 k rows x 32 bytes that 32
 //     lanes of a transpose read touch (rows k0..k0+3 and k0+8..k0+11) fall in 8 different 32-byte bank groups.
 //     For 32-wide fragments (W32, the weight-gradient product) kkey(k) = (k & 3) << 2: the 4 k rows x 4 chunks
 //     that 32 lanes touch fall in 16 different bank groups.
 // The permutation is applied on the memory side: a lane fetches the chunk that belongs at its position.
-template <bool KSTRIDED, bool W32>
+template <bool KSTRIDED, bool W32, int TILE>
 struct Operand {
+  static constexpr int NJ = Geo<TILE>::NJ, XCH = Geo<TILE>::XCH;
   const char* base;    // first byte of the tile's rows (k-contiguous) or of its first x (k-strided), at k = 0
   int64_t left;        // bytes from base to the end of the operand
-  uint32_t voff[4];    // byte offset of the lane's chunk from base, per instruction
+  uint32_t voff[NJ];   // byte offset of the lane's chunk from base, per instruction
   uint32_t k_step;     // byte distance of one k element
   int kc8;             // k-contiguous: first k of the lane's chunk inside a step
   // rows x ld elements in memory; origin: first tile row (k-contiguous) or first x (k-strided).
@@ -93,10 +100,10 @@ struct Operand {
     left = (rows * ld - first) * 2;
     kc8 = 0;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < NJ; ++j) {
       const int q = (8 * j + wave) * 64 + lane;
       if (KSTRIDED) {
-        const int krow = q >> 5, pos = q & 31;
+        const int krow = q / XCH, pos = q % XCH;
         const int c = pos ^ (W32 ? (krow & 3) << 2 : ((krow & 3) | (((krow >> 3) & 1) << 2)) << 1);
         voff[j] = ((uint32_t)krow * ld + c * 8) * 2u;
       } else {
@@ -117,14 +124,15 @@ struct Operand {
     const int64_t rest = left - skip;
     const u32x4 desc = make_desc(base + skip, (uint32_t)(rest < 0 ? 0 : (rest > 0x7fffffff ? 0x7fffffff : rest)));
 #pragma unroll
-    for (int j = 0; j < 4; ++j) load_to_lds16(desc, (lds_ptr)(tile + (8 * j + wave) * 1024), dead ? kPastEnd : voff[j]);
+    for (int j = 0; j < NJ; ++j) load_to_lds16(desc, (lds_ptr)(tile + (8 * j + wave) * 1024), dead ? kPastEnd : voff[j]);
   }
 };
 
 // MFMA operand fragment (v_mfma_f32_16x16x32_bf16: lane l holds row l % 16, k = (l / 16) * 8 .. + 7) of tile rows
 // row_base .. row_base + 15 for the k32-th group of 32 k of the step.  row_base is a multiple of 16.
-template <bool KSTRIDED>
+template <bool KSTRIDED, int TILE>
 __device__ __forceinline__ bf16x8 read_frag(const char* tile, int row_base, int k32, int lane) {
+  constexpr int KR = TILE * 2;   // bytes per k row of a k-strided tile
   if (!KSTRIDED) {
     const int lr = lane & 15, kg = lane >> 4;
     // chunk 4 k32 + kg permuted by the row's key; k32 enters by XOR with k32 * 64
@@ -136,11 +144,11 @@ __device__ __forceinline__ bf16x8 read_frag(const char* tile, int row_base, int 
     // 8g .. 8g+3, then 8g+4 .. 8g+7; both have the same kkey: (s/4) | (g & 1) << 2, shifted left by one.
     const int g = lane >> 4, s = lane & 15;
     const int key = ((s >> 2) | ((g & 1) << 2)) << 1;
-    const int lane_off = (g * 8 + (s >> 2)) * 512 + (key << 4) + (((s & 3) >> 1) << 4) + (s & 1) * 8;
-    const char* p = tile + k32 * 32 * 512 + (lane_off ^ (row_base * 2));   // row_base * 2: a multiple of 32 bytes
+    const int lane_off = (g * 8 + (s >> 2)) * KR + (key << 4) + (((s & 3) >> 1) << 4) + (s & 1) * 8;
+    const char* p = tile + k32 * 32 * KR + (lane_off ^ (row_base * 2));   // row_base * 2: a multiple of 32 bytes
     typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
     s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
-    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * 512));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * KR));
     typedef __attribute__((ext_vector_type(8))) short s16x8;
     s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
     return __builtin_bit_cast(bf16x8, v);
@@ -150,8 +158,9 @@ __device__ __forceinline__ bf16x8 read_frag(const char* tile, int row_base, int 
 // The same for v_mfma_f32_32x32x16_bf16 (the weight-gradient product keeps this form: its accumulator layout
 // gives atomics that cover 128 contiguous bytes).  Fragment of tile row `row_base + lane % 32` for k-step ks (16 k): 8 consecutive k, starting at
 // ks*16 + (lane/32)*8.  row_base is a multiple of 32.
-template <bool KSTRIDED>
+template <bool KSTRIDED, int TILE>
 __device__ __forceinline__ bf16x8 read_frag32(const char* tile, int row_base, int ks, int lane) {
+  constexpr int KR = TILE * 2;
   if (!KSTRIDED) {
     const int lr = lane & 31, hh = lane >> 5;
     // chunk 2 ks + hh permuted by the row's key; ks enters by XOR with ks * 32
@@ -161,11 +170,11 @@ __device__ __forceinline__ bf16x8 read_frag32(const char* tile, int row_base, in
     // group of 16 lanes = 16 consecutive x; lane s of the group addresses k row s/4, x piece s%4:
     // k row ks*16 + hh*8 + i (and + 4), chunk row_base/8 + 2 g16 + (s%4)/2, permuted by i << 2
     const int g16 = (lane >> 4) & 1, hh = lane >> 5, s = lane & 15, i = s >> 2;
-    const int lane_off = (hh * 8 + i) * 512 + (((i << 2) | (g16 * 2 + ((s & 3) >> 1))) << 4) + (s & 1) * 8;
-    const char* p = tile + ks * 16 * 512 + (lane_off ^ (row_base * 2));   // row_base * 2 = chunk bits 2.. : multiple of 64
+    const int lane_off = (hh * 8 + i) * KR + (((i << 2) | (g16 * 2 + ((s & 3) >> 1))) << 4) + (s & 1) * 8;
+    const char* p = tile + ks * 16 * KR + (lane_off ^ (row_base * 2));   // row_base * 2 = chunk bits 2.. : multiple of 64
     typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
     s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
-    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * 512));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * KR));
     typedef __attribute__((ext_vector_type(8))) short s16x8;
     s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
     return __builtin_bit_cast(bf16x8, v);
@@ -173,12 +182,15 @@ __device__ __forceinline__ bf16x8 read_frag32(const char* tile, int row_base, in
 }
 
 // ROPE (op 0 only): the leading rope.rot_cols columns of the output are rotated on the way out
-template <int OP, bool KMASK, bool ROPE = false>
+template <int OP, bool KMASK, bool ROPE, int TILE>
 __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ B,
                                                         void* __restrict__ Cv, const bf16* __restrict__ Rr, int M,
                                                         int N, int K, int tiles_m, int tiles_n, RopeArgs rope) {
   constexpr bool AS = OP == 2, BS = OP != 0;   // which operands are k-strided
-  __shared__ __attribute__((aligned(1024))) char smem[kLdsBytes];
+  typedef Geo<TILE> G;
+  constexpr int kTileBytes = G::kTileBytes, kStageBytes = G::kStageBytes, kCRowBytes = G::kCRowBytes;
+  constexpr int WM = G::WM, WN = G::WN, BM = TILE, BN = TILE;
+  __shared__ __attribute__((aligned(1024))) char smem[G::kLdsBytes];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 2, wn = wave & 3;
@@ -212,27 +224,28 @@ __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__
   const int nk = ks1 - ks0;
 
   constexpr bool W32 = OP == 2;   // which MFMA form (see read_frag32)
-  Operand<AS, W32> opa;
-  Operand<BS, W32> opb;
+  Operand<AS, W32, TILE> opa;
+  Operand<BS, W32, TILE> opb;
   opa.init(A, AS ? K : M, AS ? M : K, m0, wave, lane);
   opb.init(B, BS ? K : N, BS ? N : K, n0, wave, lane);
 
-  // OP 0/1: acc[j][i] = 16 output rows m (j of 8) x 16 output columns n (i of 4) of the wavefront's 128 x 64.
-  // OP 2: acc32[j][i] = 32 rows (j of 4) x 32 columns (i of 2).
-  f32x4 acc[W32 ? 1 : 8][W32 ? 1 : 4];
-  f32x16 acc32[W32 ? 4 : 1][W32 ? 2 : 1];
+  // OP 0/1: acc[j][i] = 16 output rows m x 16 output columns n of the wavefront's WM x WN share.
+  // OP 2: acc32[j][i] = 32 rows x 32 columns of it.
+  constexpr int NJ16 = WM / 16, NI16 = WN / 16, NJ32 = WM / 32, NI32 = WN / 32;
+  f32x4 acc[W32 ? 1 : NJ16][W32 ? 1 : NI16];
+  f32x16 acc32[W32 ? NJ32 : 1][W32 ? NI32 : 1];
   if (W32) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < NJ32; ++j)
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < NI32; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc32[W32 ? j : 0][W32 ? i : 0][r] = 0.f;
   } else {
 #pragma unroll
-    for (int j = 0; j < 8; ++j)
+    for (int j = 0; j < NJ16; ++j)
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+      for (int i = 0; i < NI16; ++i)
 #pragma unroll
         for (int r = 0; r < 4; ++r) acc[W32 ? 0 : j][W32 ? 0 : i][r] = 0.f;
   }
@@ -243,30 +256,30 @@ __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__
     if (W32) {
 #pragma unroll
       for (int ks = 0; ks < BK / 16; ++ks) {
-        bf16x8 fa[4], fb[2];
+        bf16x8 fa[NJ32], fb[NI32];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) fa[j] = read_frag32<AS>(ta, wm * 128 + j * 32, ks, lane);
+        for (int j = 0; j < NJ32; ++j) fa[j] = read_frag32<AS, TILE>(ta, wm * WM + j * 32, ks, lane);
 #pragma unroll
-        for (int i = 0; i < 2; ++i) fb[i] = read_frag32<BS>(tb, wn * 64 + i * 32, ks, lane);
+        for (int i = 0; i < NI32; ++i) fb[i] = read_frag32<BS, TILE>(tb, wn * WN + i * 32, ks, lane);
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < NJ32; ++j)
 #pragma unroll
-          for (int i = 0; i < 2; ++i)
+          for (int i = 0; i < NI32; ++i)
             acc32[W32 ? j : 0][W32 ? i : 0] =
                 __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[j], fb[i], acc32[W32 ? j : 0][W32 ? i : 0], 0, 0, 0);
       }
     } else {
 #pragma unroll
       for (int k32 = 0; k32 < BK / 32; ++k32) {
-        bf16x8 fa[8], fb[4];
+        bf16x8 fa[NJ16], fb[NI16];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) fa[j] = read_frag<AS>(ta, wm * 128 + j * 16, k32, lane);
+        for (int j = 0; j < NJ16; ++j) fa[j] = read_frag<AS, TILE>(ta, wm * WM + j * 16, k32, lane);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) fb[i] = read_frag<BS>(tb, wn * 64 + i * 16, k32, lane);
+        for (int i = 0; i < NI16; ++i) fb[i] = read_frag<BS, TILE>(tb, wn * WN + i * 16, k32, lane);
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
+        for (int j = 0; j < NJ16; ++j)
 #pragma unroll
-          for (int i = 0; i < 4; ++i)
+          for (int i = 0; i < NI16; ++i)
             acc[W32 ? 0 : j][W32 ? 0 : i] =
                 __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[i], fa[j], acc[W32 ? 0 : j][W32 ? 0 : i], 0, 0, 0);
       }
@@ -301,13 +314,13 @@ __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__
     // contiguous bytes of two rows.
     float* C = reinterpret_cast<float*>(Cv);
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < NJ32; ++j)
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const int col = n0 + wn * 64 + i * 32 + (lane & 31);
+      for (int i = 0; i < NI32; ++i) {
+        const int col = n0 + wn * WN + i * 32 + (lane & 31);
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int row = m0 + wm * 128 + j * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+          const int row = m0 + wm * WM + j * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
           if (row < M && col < N) {
             float* p = C + (int64_t)row * N + col;
             unsafeAtomicAdd(p, acc32[W32 ? j : 0][W32 ? i : 0][r]);
@@ -317,21 +330,21 @@ __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__
   } else {
     // all wavefronts are past the last barrier of the loop: the operand buffers are free
 #pragma unroll
-    for (int j = 0; j < 8; ++j)
+    for (int j = 0; j < NJ16; ++j)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < NI16; ++i) {
         uint2 w;
         w.x = pack_bf16(acc[W32 ? 0 : j][W32 ? 0 : i][0], acc[W32 ? 0 : j][W32 ? 0 : i][1]);
         w.y = pack_bf16(acc[W32 ? 0 : j][W32 ? 0 : i][2], acc[W32 ? 0 : j][W32 ? 0 : i][3]);
-        *reinterpret_cast<uint2*>(smem + (wm * 128 + j * 16 + lm) * kCRowBytes + (wn * 64 + i * 16 + kg * 4) * 2) = w;
+        *reinterpret_cast<uint2*>(smem + (wm * WM + j * 16 + lm) * kCRowBytes + (wn * WN + i * 16 + kg * 4) * 2) = w;
       }
     __syncthreads();
     bf16* C = reinterpret_cast<bf16*>(Cv);
     const bool add = OP == 0 && Rr != nullptr;
 #pragma unroll 4
-    for (int it = 0; it < 16; ++it) {
+    for (int it = 0; it < TILE * TILE / 8 / kThreads; ++it) {
       const int c = tid + kThreads * it;
-      const int row = c >> 5, nc = c & 31;
+      const int row = c / (TILE / 8), nc = c % (TILE / 8);
       const int grow = m0 + row, gcol = n0 + nc * 8;
       if (grow < M && gcol < N) {   // N is a multiple of 8: a chunk is inside or outside as a whole
         uint4 v = *reinterpret_cast<const uint4*>(smem + row * kCRowBytes + nc * 16);
@@ -392,7 +405,7 @@ bool gemm_mfma_supported(int op, int64_t M, int64_t N, int64_t K, const void* A,
   // tile-relative byte offsets (up to 256 rows of the leading dimension) stay below 2^31
   if (M >= (1 << 21) || N >= (1 << 21) || K >= (1 << 21)) return false;
   if (!al16(A) || !al16(B) || !al16(C) || (R && !al16(R))) return false;
-  if (((M + BM - 1) / BM) * ((N + BN - 1) / BN) > (1 << 24)) return false;
+  if (((M + 127) / 128) * ((N + 127) / 128) > (1 << 24)) return false;
   if (N % 8) return false;                      // 16-byte output chunks
   switch (op) {
     case 0: return K % 8 == 0;
@@ -404,11 +417,15 @@ bool gemm_mfma_supported(int op, int64_t M, int64_t N, int64_t K, const void* A,
 
 void gemm_mfma(hipStream_t s, int op, int64_t M, int64_t N, int64_t K, const void* A, const void* B, void* C,
                const void* R, const RopeArgs* rope) {
-  const int tm = (int)((M + BM - 1) / BM), tn = (int)((N + BN - 1) / BN);
-  const int tiles = tm * tn;
   // The chip delivers about the same aggregate rate with two thirds of its CUs busy as with all of them
   // (the kernel is bound by what the L2s and the power budget give), but a nearly empty round is lost time.
   const int cus = cu_count();
+  // 256 x 256 tiles move the fewest bytes per flop; a product with too few of them to occupy the CUs
+  // (a single microbatch through a narrow layer) takes 128 x 128 tiles instead
+  const int64_t big = ((M + 255) / 256) * ((N + 255) / 256);
+  const int tile = (op != 2 && big * 4 < (int64_t)cus * 3) ? 128 : 256;
+  const int tm = (int)((M + tile - 1) / tile), tn = (int)((N + tile - 1) / tile);
+  const int tiles = tm * tn;
   int wgs;
   if (op == 2) {
     // a whole number s of runs per tile, so that the runs of neighbouring tiles walk the same k range
@@ -433,12 +450,15 @@ void gemm_mfma(hipStream_t s, int op, int64_t M, int64_t N, int64_t K, const voi
   const bf16* r = (const bf16*)R;
   const bool kmask = K % BK != 0;
   const RopeArgs ra = rope ? *rope : RopeArgs{nullptr, 1, 8, 0};
-#define SP_LAUNCH(OP, KM, RP) \
-  hipLaunchKernelGGL((k_gemm_mfma<OP, KM, RP>), grid, dim3(kThreads), 0, s, a, b, C, r, (int)M, (int)N, (int)K, tm, tn, ra)
-  if (op == 0 && rope) { if (kmask) SP_LAUNCH(0, true, true); else SP_LAUNCH(0, false, true); }
-  else if (op == 0) { if (kmask) SP_LAUNCH(0, true, false); else SP_LAUNCH(0, false, false); }
-  else if (op == 1) { if (kmask) SP_LAUNCH(1, true, false); else SP_LAUNCH(1, false, false); }
-  else SP_LAUNCH(2, false, false);
+#define SP_LAUNCH(OP, KM, RP, TL) \
+  hipLaunchKernelGGL((k_gemm_mfma<OP, KM, RP, TL>), grid, dim3(kThreads), 0, s, a, b, C, r, (int)M, (int)N, (int)K, tm, tn, ra)
+#define SP_LAUNCH_T(OP, KM, RP) \
+  do { if (tile == 128) SP_LAUNCH(OP, KM, RP, 128); else SP_LAUNCH(OP, KM, RP, 256); } while (0)
+  if (op == 0 && rope) { if (kmask) SP_LAUNCH_T(0, true, true); else SP_LAUNCH_T(0, false, true); }
+  else if (op == 0) { if (kmask) SP_LAUNCH_T(0, true, false); else SP_LAUNCH_T(0, false, false); }
+  else if (op == 1) { if (kmask) SP_LAUNCH_T(1, true, false); else SP_LAUNCH_T(1, false, false); }
+  else SP_LAUNCH(2, false, false, 256);
+#undef SP_LAUNCH_T
 #undef SP_LAUNCH
 }
 

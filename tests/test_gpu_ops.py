@@ -19,6 +19,7 @@ def dev(a, dt):
 GEMM_SHAPES = [
     (256, 256, 64), (512, 768, 256), (300, 520, 136), (64, 288, 288), (1, 8, 8), (257, 264, 72),
     (1000, 40, 1024), (128, 864, 288), (2048, 2048, 512), (72, 1032, 2056),
+    (4096, 3848, 136),     # enough 256 x 256 tiles for the large-tile path; the smaller shapes take 128 x 128 tiles
 ]
 
 
