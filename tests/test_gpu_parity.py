@@ -265,3 +265,16 @@ def test_scheduled_paths_run_through_the_model():
     ref = orc.run_paths(cfg, named, paths, lens, tokens=tok, targets=tgt, dtype=np.float64)
     got = run(cfg, named, paths, lens, tokens=tok, targets=tgt)
     check_f32(got, ref, "scheduled paths")
+
+
+def test_contexts_can_be_created_and_destroyed_repeatedly():
+    # every context owns a workspace, a side stream and events: none of them may be left behind
+    cfg = dict(SMALL, dtype="bf16")
+    sp.Context(cfg, 2, 4).close()                 # first use loads code objects and the like
+    torch.cuda.synchronize()
+    free0 = torch.cuda.mem_get_info()[0]
+    for _ in range(40):
+        c = sp.Context(cfg, 2, 4)
+        c.close()
+    torch.cuda.synchronize()
+    assert torch.cuda.mem_get_info()[0] >= free0 - (8 << 20)
