@@ -472,24 +472,6 @@ __global__ __launch_bounds__(256, 2) void k_flash_bwd_dq(const bf16* __restrict_
 // wavefront waits for its own (vmcnt, counted by hand) before the barrier after which a tile is first read.
 // Rows past the end of the sequence and tiles past the end of the walk read as zeros (offsets beyond
 // the buffer descriptors), and zero rows of Q and dO contribute nothing to either gradient.
-// Buffer loads with the LDS modifier, written as assembly so that the compiler's wait insertion does not
-// see them: it would otherwise make the first LDS read after every such load wait for it (it cannot tell
-// that the read is from another ring buffer), which would undo the prefetch.  One instruction copies
-// 64 x 16 bytes (or 64 x 4) from the lanes' buffer offsets to LDS at lds .. lds + 1024 (256) in lane
-// order; offsets at or past the descriptor's size deliver zeros.  Tracked by vmcnt like any load.
-typedef __attribute__((address_space(3))) void* lds_ptr;
-__device__ __forceinline__ u32x4 make_desc(const void* p, uint32_t bytes) {
-  const uint64_t a = (uint64_t)p;
-  u32x4 d = {(uint32_t)a, (uint32_t)(a >> 32) & 0xffffu, bytes, 0x00020000u};
-  return d;
-}
-__device__ __forceinline__ void load_to_lds16(u32x4 desc, lds_ptr lds, uint32_t voff) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds), "v"(voff), "s"(desc) : "memory");
-}
-__device__ __forceinline__ void load_to_lds4(u32x4 desc, lds_ptr lds, uint32_t voff) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds" ::"s"(lds), "v"(voff), "s"(desc) : "memory");
-}
-
 template <int HD>
 struct DkvGeom {
   static constexpr int BQ = 32, NK = HD / 16, NC = HD / 32;

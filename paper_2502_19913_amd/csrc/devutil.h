@@ -58,6 +58,25 @@ __device__ __forceinline__ u32x4 buffer_load16(rsrc_t rsrc, uint32_t voff) {
   return __builtin_bit_cast(u32x4, (i32x4_)__builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)voff, 0, 0));
 }
 
+// ---- buffer loads with the LDS modifier (memory -> LDS without passing through registers), written as
+// assembly so that the compiler's wait insertion does not see them: it would otherwise make the first LDS
+// read after every such load wait for it (it cannot tell that the read is from another buffer), which would
+// undo any prefetch.  One instruction copies 64 x 16 bytes (or 64 x 4) from the lanes' buffer offsets to LDS at
+// lds .. lds + 1024 (256) in lane order; an offset at or past the descriptor's size delivers zeros.  Counted
+// by vmcnt like any load: the caller waits for them by hand (s_waitcnt) before a barrier.
+typedef __attribute__((address_space(3))) void* lds_ptr;
+__device__ __forceinline__ u32x4 make_desc(const void* p, uint32_t bytes) {   // raw buffer descriptor as 4 words
+  const uint64_t a = (uint64_t)p;
+  u32x4 d = {(uint32_t)a, (uint32_t)(a >> 32) & 0xffffu, bytes, 0x00020000u};
+  return d;
+}
+__device__ __forceinline__ void load_to_lds16(u32x4 desc, lds_ptr lds, uint32_t voff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds), "v"(voff), "s"(desc) : "memory");
+}
+__device__ __forceinline__ void load_to_lds4(u32x4 desc, lds_ptr lds, uint32_t voff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds" ::"s"(lds), "v"(voff), "s"(desc) : "memory");
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);

@@ -59,19 +59,6 @@ struct Geo {
   static constexpr int WM = TILE / 2, WN = TILE / 4;      // a wavefront's share of the tile (2 x 4 wavefronts)
 };
 
-// Buffer loads with the LDS modifier, written as assembly so that the compiler's wait insertion does not
-// see them (it would make the first LDS read after each of them wait for it).  One instruction copies
-// 64 x 16 bytes from the lanes' buffer offsets to LDS at lds .. lds + 1024 in lane order; an offset at or
-// past the descriptor's size delivers zeros.  Counted by vmcnt like any load.
-typedef __attribute__((address_space(3))) void* lds_ptr;
-__device__ __forceinline__ u32x4 make_desc(const void* p, uint32_t bytes) {
-  const uint64_t a = (uint64_t)p;
-  u32x4 d = {(uint32_t)a, (uint32_t)(a >> 32) & 0xffffu, bytes, 0x00020000u};
-  return d;
-}
-__device__ __forceinline__ void load_to_lds16(u32x4 desc, lds_ptr lds, uint32_t voff) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds), "v"(voff), "s"(desc) : "memory");
-}
 constexpr uint32_t kPastEnd = 0x80000000u;      // no descriptor is this large
 
 // One operand's share of the tile loads for one wavefront: TILE / 64 instructions of 1 KiB per step.
