@@ -54,12 +54,29 @@ struct Geo {
   static constexpr int kStageBytes = 2 * kTileBytes;      // A and B
   static constexpr int kCRowBytes = TILE * 2 + 16;        // output staging row: TILE bf16 + 16 bytes
   static constexpr int kLdsBytes = TILE * kCRowBytes > 2 * kStageBytes ? TILE * kCRowBytes : 2 * kStageBytes;
+  static constexpr int kLdsBytesPP = 5 * kTileBytes;     // alternating-phase loop: two tiles of A, three of B
   static constexpr int NJ = kTileBytes / 1024 / 8;        // load instructions per wavefront and operand tile
   static constexpr int XCH = TILE / 8;                    // 16-byte chunks per k row of a k-strided tile
   static constexpr int WM = TILE / 2, WN = TILE / 4;      // a wavefront's share of the tile (2 x 4 wavefronts)
 };
 
 constexpr uint32_t kPastEnd = 0x80000000u;      // no descriptor is this large
+
+// Byte offset, from the tile's first row (k-contiguous) or first x (k-strided) at the step's first k, of the
+// 16-byte chunk that belongs at position q of the tile in LDS (layouts above); kc8: for k-contiguous tiles, the
+// first k of that chunk inside the step.
+template <bool KSTRIDED, bool W32, int TILE>
+__device__ __forceinline__ uint32_t chunk_offset(int q, int ld, int& kc8) {
+  constexpr int XCH = Geo<TILE>::XCH;
+  if (KSTRIDED) {
+    const int krow = q / XCH, pos = q % XCH;
+    const int c = pos ^ (W32 ? (krow & 3) << 2 : ((krow & 3) | (((krow >> 3) & 1) << 2)) << 1);
+    return ((uint32_t)krow * ld + c * 8) * 2u;
+  }
+  const int row = q >> 3, pos = q & 7, c = pos ^ ((row >> 1) & 7);
+  kc8 = c * 8;
+  return ((uint32_t)row * ld + c * 8) * 2u;
+}
 
 // One operand's share of the tile loads for one wavefront: TILE / 64 instructions of 1 KiB per step.
 // Instruction j fills the tile's 16-byte chunks (8j + wave) * 64 + lane.
@@ -89,15 +106,7 @@ struct Operand {
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
       const int q = (8 * j + wave) * 64 + lane;
-      if (KSTRIDED) {
-        const int krow = q / XCH, pos = q % XCH;
-        const int c = pos ^ (W32 ? (krow & 3) << 2 : ((krow & 3) | (((krow >> 3) & 1) << 2)) << 1);
-        voff[j] = ((uint32_t)krow * ld + c * 8) * 2u;
-      } else {
-        const int row = q >> 3, pos = q & 7, c = pos ^ ((row >> 1) & 7);
-        voff[j] = ((uint32_t)row * ld + c * 8) * 2u;
-        kc8 = c * 8;   // the same for every j: it depends on lane and wave & 1 only
-      }
+      voff[j] = chunk_offset<KSTRIDED, W32, TILE>(q, ld, kc8);   // kc8: the same for every j (lane and wave & 1 only)
     }
     k_step = KSTRIDED ? (uint32_t)ld * 2u : 2u;
   }
@@ -112,6 +121,49 @@ struct Operand {
     const u32x4 desc = make_desc(base + skip, (uint32_t)(rest < 0 ? 0 : (rest > 0x7fffffff ? 0x7fffffff : rest)));
 #pragma unroll
     for (int j = 0; j < NJ; ++j) load_to_lds16(desc, (lds_ptr)(tile + (8 * j + wave) * 1024), dead ? kPastEnd : voff[j]);
+  }
+};
+
+// The loads of one wavefront when a workgroup's halves divide the operands between them (the alternating-phase
+// loop): wavefronts 0-3 load the tiles of A, wavefronts 4-7 those of B, so a wavefront issues a quarter of one
+// operand's tile, instruction j filling chunks (4 j + w4) * 64 + lane.  One set of offsets serves either role.
+template <bool AS, bool BS, bool W32, int TILE>
+struct HalfLoader {
+  static constexpr int NJ = Geo<TILE>::kTileBytes / 1024 / 4;
+  const char* base;
+  int64_t left;
+  uint32_t voff[NJ];
+  uint32_t k_step;
+  int kc8;
+  bool strided;
+  __device__ __forceinline__ void init(bool late, const bf16* A, int64_t a_rows, int a_ld, int a_origin, const bf16* B,
+                                       int64_t b_rows, int b_ld, int b_origin, int w4, int lane) {
+    const bf16* X = late ? B : A;
+    const int64_t rows = late ? b_rows : a_rows;
+    const int ld = late ? b_ld : a_ld, origin = late ? b_origin : a_origin;
+    strided = late ? BS : AS;
+    const int64_t first = strided ? (int64_t)origin : (int64_t)origin * ld;
+    base = reinterpret_cast<const char*>(X + first);
+    left = (rows * ld - first) * 2;
+    kc8 = 0;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      const int q = (4 * j + w4) * 64 + lane;
+      int kc_a = 0, kc_b = 0;
+      const uint32_t oa = chunk_offset<AS, W32, TILE>(q, ld, kc_a), ob = AS == BS ? oa : chunk_offset<BS, W32, TILE>(q, ld, kc_b);
+      voff[j] = late ? ob : oa;
+      kc8 = late ? (AS == BS ? kc_a : kc_b) : kc_a;
+    }
+    k_step = strided ? (uint32_t)ld * 2u : 2u;
+  }
+  template <bool KMASK>
+  __device__ __forceinline__ void load(int k0, int kend, char* tile, int w4) const {
+    const bool dead = KMASK && !strided && (k0 + kc8 >= kend);
+    const int64_t skip = (int64_t)k0 * k_step;
+    const int64_t rest = left - skip;
+    const u32x4 desc = make_desc(base + skip, (uint32_t)(rest < 0 ? 0 : (rest > 0x7fffffff ? 0x7fffffff : rest)));
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) load_to_lds16(desc, (lds_ptr)(tile + (4 * j + w4) * 1024), dead ? kPastEnd : voff[j]);
   }
 };
 
@@ -169,7 +221,7 @@ __device__ __forceinline__ bf16x8 read_frag32(const char* tile, int row_base, in
 }
 
 // ROPE (op 0 only): the leading rope.rot_cols columns of the output are rotated on the way out
-template <int OP, bool KMASK, bool ROPE, int TILE>
+template <int OP, bool KMASK, bool ROPE, int TILE, bool PP = false>
 __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ B,
                                                         void* __restrict__ Cv, const bf16* __restrict__ Rr, int M,
                                                         int N, int K, int tiles_m, int tiles_n, RopeArgs rope) {
@@ -177,7 +229,7 @@ __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__
   typedef Geo<TILE> G;
   constexpr int kTileBytes = G::kTileBytes, kStageBytes = G::kStageBytes, kCRowBytes = G::kCRowBytes;
   constexpr int WM = G::WM, WN = G::WN, BM = TILE, BN = TILE;
-  __shared__ __attribute__((aligned(1024))) char smem[G::kLdsBytes];
+  __shared__ __attribute__((aligned(1024))) char smem[PP ? G::kLdsBytesPP : G::kLdsBytes];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 2, wn = wave & 3;
@@ -284,12 +336,99 @@ __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__
     __builtin_amdgcn_s_barrier();
   };
 
-  issue(0);
-  landed_barrier();
-  for (int kt = 0; kt < nk; ++kt) {
-    if (kt + 1 < nk) issue(kt + 1);   // into the stage every wavefront left before the last barrier
-    compute(smem + (kt & 1) * kStageBytes);
+  if (!PP) {
+    issue(0);
     landed_barrier();
+    for (int kt = 0; kt < nk; ++kt) {
+      if (kt + 1 < nk) issue(kt + 1);   // into the stage every wavefront left before the last barrier
+      compute(smem + (kt & 1) * kStageBytes);
+      landed_barrier();
+    }
+  } else {
+    // Two wavefronts share a SIMD (w and w + 4).  They alternate between a memory phase (all fragments of one
+    // k-step from LDS into registers, loads of a later step issued) and a compute phase (the step's MFMAs, back
+    // to back from registers), half a step apart, so that a SIMD's matrix core always has one wavefront
+    // feeding it while the other waits for LDS and for the load queue.  Every phase ends at a workgroup
+    // barrier; the late half executes one more barrier before its first phase and the early half one more
+    // after its last.  The early half loads the tiles of A one step ahead into two buffers, the late half the
+    // tiles of B two steps ahead into three, so every load has two phases to land before anyone waits for it
+    // and the load unit sees the same number of instructions in every phase.
+    const bool late = wave >= 4;
+    const int w4 = wave & 3;
+    constexpr int kLgkm0 = 0xC07F, kVm0 = 0x0F70;
+    char* const a_ring = smem;                       // 2 tiles
+    char* const b_ring = smem + 2 * kTileBytes;      // 3 tiles
+    HalfLoader<AS, BS, W32, TILE> mine;
+    mine.init(late, A, AS ? K : M, AS ? M : K, m0, B, BS ? K : N, BS ? N : K, n0, w4, lane);
+    auto issue_a = [&](int t) { mine.template load<KMASK>(kb + t * BK, kend, a_ring + (t & 1) * kTileBytes, w4); };
+    auto issue_b = [&](int t, int slot) { mine.template load<KMASK>(kb + t * BK, kend, b_ring + slot * kTileBytes, w4); };
+    if (!late) issue_a(0);
+    else { issue_b(0, 0); if (nk > 1) issue_b(1, 1); }
+    __builtin_amdgcn_s_waitcnt(kVm0);
+    __builtin_amdgcn_s_barrier();
+    if (late) __builtin_amdgcn_s_barrier();
+    int bs = 0;   // kt mod 3
+    for (int kt = 0; kt < nk; ++kt) {
+      const char* ta = a_ring + (kt & 1) * kTileBytes;
+      const char* tb = b_ring + bs * kTileBytes;
+      if (W32) {
+        bf16x8 fa[BK / 16][NJ32], fb[BK / 16][NI32];
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+#pragma unroll
+          for (int j = 0; j < NJ32; ++j) fa[ks][j] = read_frag32<AS, TILE>(ta, wm * WM + j * 32, ks, lane);
+#pragma unroll
+          for (int i = 0; i < NI32; ++i) fb[ks][i] = read_frag32<BS, TILE>(tb, wn * WN + i * 32, ks, lane);
+        }
+        if (!late) { if (kt + 1 < nk) issue_a(kt + 1); }
+        else if (kt + 2 < nk) issue_b(kt + 2, bs == 0 ? 2 : bs - 1);
+        __builtin_amdgcn_s_waitcnt(kLgkm0);
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks)
+#pragma unroll
+          for (int j = 0; j < NJ32; ++j)
+#pragma unroll
+            for (int i = 0; i < NI32; ++i)
+              acc32[W32 ? j : 0][W32 ? i : 0] =
+                  __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks][j], fb[ks][i], acc32[W32 ? j : 0][W32 ? i : 0], 0, 0, 0);
+        __builtin_amdgcn_s_setprio(0);
+      } else {
+        bf16x8 fa[BK / 32][NJ16], fb[BK / 32][NI16];
+#pragma unroll
+        for (int k32 = 0; k32 < BK / 32; ++k32) {
+#pragma unroll
+          for (int j = 0; j < NJ16; ++j) fa[k32][j] = read_frag<AS, TILE>(ta, wm * WM + j * 16, k32, lane);
+#pragma unroll
+          for (int i = 0; i < NI16; ++i) fb[k32][i] = read_frag<BS, TILE>(tb, wn * WN + i * 16, k32, lane);
+        }
+        if (!late) { if (kt + 1 < nk) issue_a(kt + 1); }
+        else if (kt + 2 < nk) issue_b(kt + 2, bs == 0 ? 2 : bs - 1);
+        __builtin_amdgcn_s_waitcnt(kLgkm0);
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+        for (int k32 = 0; k32 < BK / 32; ++k32)
+#pragma unroll
+          for (int j = 0; j < NJ16; ++j)
+#pragma unroll
+            for (int i = 0; i < NI16; ++i)
+              acc[W32 ? 0 : j][W32 ? 0 : i] =
+                  __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[k32][i], fa[k32][j], acc[W32 ? 0 : j][W32 ? 0 : i], 0, 0, 0);
+        __builtin_amdgcn_s_setprio(0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      __builtin_amdgcn_s_waitcnt(kVm0);   // issued two phases ago
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_sched_barrier(0);
+      bs = bs == 2 ? 0 : bs + 1;
+    }
+    if (!late) __builtin_amdgcn_s_barrier();
   }
 
   // ---- epilogue.  With the tile of B as the MFMA's row operand (OP 0/1), accumulator r of lane l is output
@@ -438,7 +577,7 @@ void gemm_mfma(hipStream_t s, int op, int64_t M, int64_t N, int64_t K, const voi
   const bool kmask = K % BK != 0;
   const RopeArgs ra = rope ? *rope : RopeArgs{nullptr, 1, 8, 0};
 #define SP_LAUNCH(OP, KM, RP, TL) \
-  hipLaunchKernelGGL((k_gemm_mfma<OP, KM, RP, TL>), grid, dim3(kThreads), 0, s, a, b, C, r, (int)M, (int)N, (int)K, tm, tn, ra)
+  hipLaunchKernelGGL((k_gemm_mfma<OP, KM, RP, TL, TL == 256>), grid, dim3(kThreads), 0, s, a, b, C, r, (int)M, (int)N, (int)K, tm, tn, ra)
 #define SP_LAUNCH_T(OP, KM, RP) \
   do { if (tile == 128) SP_LAUNCH(OP, KM, RP, 128); else SP_LAUNCH(OP, KM, RP, 256); } while (0)
   if (op == 0 && rope) { if (kmask) SP_LAUNCH_T(0, true, true); else SP_LAUNCH_T(0, false, true); }
