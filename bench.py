@@ -42,11 +42,12 @@ def build_workload(key, torch, sp, synth):
     gen.manual_seed(synth.BASE_SEED)
     n_mb, Nmb, d = cfg["n_mb"], cfg["seqs_per_mb"] * cfg["seq_len"], cfg["dim"]
     whole = bool(cfg["has_embed"] and cfg["has_head"])
+    # paths come from the library's exported generator (sp_make_paths)
     if whole:
-        paths, lens = synth.make_paths(cfg["n_stages"], n_mb, *cfg["skip"], bool(cfg["swap"]), synth.BASE_SEED)
+        paths, lens = sp.make_paths(cfg["n_stages"], n_mb, *cfg["skip"], bool(cfg["swap"]), synth.BASE_SEED)
         stage = None
     else:
-        paths, lens, stage = synth.stage_share_paths(key)
+        paths, lens, stage = synth.stage_share_paths(key, generator=sp.make_paths)
         cfg["local_stage_begin"], cfg["local_stage_count"] = stage, 1
     plan = sp.route_plan(cfg, paths, lens)
     visits = sum(len(m) for _, _, m in plan)

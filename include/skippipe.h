@@ -110,8 +110,13 @@ int64_t sp_workspace_bytes(const sp_cfg* cfg, int n_mb_max, int n_visits_max);
 int sp_make_paths(int n_stages, int n_mb, int skip_num, int skip_den, int allow_swap, uint64_t seed,
                   int32_t* paths, int32_t* len);
 
-/* Checks caller paths (host arrays as above) against cfg->path_flags: stage 0 first, no repeats,
- * indices in range, order rule.  SP_EPATH names the first violation through sp_strerror. */
+/* Checks caller paths (host arrays as above) against the convergence constraints of "Guideline for
+ * Partial Pipelining Scheduler" in the form cfg->path_flags selects: CC1 stage 0 first; CC2 the order rule
+ * (increasing, at most one exchange of two neighbouring entries; the printed |i_j - i_j+1| <= 1 cannot hold
+ * on a path with a skip and is read this way); plus what a path is by definition ("Partial and Reordered
+ * Pipelining"): no stage twice, indices in range, length in [1, n_stages].  CC3 (every later stage skipped equally
+ * often) is a property of a path set that sp_make_paths guarantees and this check does not demand of caller
+ * paths.  SP_EPATH names the first violation through sp_strerror. */
 int sp_check_paths(const sp_cfg* cfg, const int32_t* paths, const int32_t* len, int n_mb);
 
 /* Route plan (section "Partial and Reordered Pipelining": several microbatches may share a path, and a
@@ -122,6 +127,28 @@ int sp_check_paths(const sp_cfg* cfg, const int32_t* paths, const int32_t* len, 
 int sp_route_plan(const sp_cfg* cfg, const int32_t* paths, const int32_t* len, int n_mb, int32_t* group_pos,
                   int32_t* group_stage, int32_t* group_begin, int32_t* group_mb, int cap_groups, int* n_groups);
 
+/* Nodes per stage by the node distribution rule (section "Allocating Nodes to Stages", Eq. 1): later stages
+ * see only a share 1 - s/(s-1) k of the microbatches, so |S_i| = |S_0| (1 - s/(s-1) k) for i >= 1.  sizes: host
+ * int32 [n_stages]; every node is used; the later stages get the nearest whole number, stage 0 the rest.
+ * SP_EINVAL if fewer nodes than stages or the ratio leaves the later stages nothing. */
+int sp_stage_sizes(int n_nodes, int n_stages, int skip_num, int skip_den, int32_t* sizes);
+
+typedef struct sp_sched_problem {
+  int32_t n_stages, n_nodes, n_agents;
+  int32_t mem_limit;   /* m of TC1 */
+  int32_t strict_swap; /* CC2: exchanged stages must be consecutive */
+  int32_t no_swap;     /* != 0: stages strictly in increasing order (no exchange at all) */
+  int32_t n_solutions, max_expansions;
+  float delta;
+  float focal_slack;   /* second phase: among solutions within this fraction of the cheapest, the one with the
+                          fewest collisions is expanded next; 0 = strictly cheapest first (the paper); < 0 = 0.5 */
+  const int32_t* node_stage;
+  const float* compute_fwd;
+  const float* compute_bwd;
+  const float* comm;
+  const int32_t* start_node;
+  const int32_t* n_keep;
+} sp_sched_problem;
 /* Path scheduler (sections "Partial and Reordered Pipelining" and "Path finding", appendix "Detailed Path
  * Selection Algorithm"): for the first wave of microbatches (agents), which node of which stage each visits
  * and when, so that the slowest agent's end-to-end latency is small under the paper's constraints:
@@ -149,28 +176,6 @@ int sp_route_plan(const sp_cfg* cfg, const int32_t* paths, const int32_t* len, i
  * may be null); e2e [n_agents] and max_e2e (may be null).  SP_EPATH: no conflict-free solution found within
  * max_expansions (20000 if <= 0) constraint-tree expansions; SP_EINVAL: bad sizes, a start node outside
  * stage 0, a stage without nodes, negative times. */
-/* Nodes per stage by the node distribution rule (section "Allocating Nodes to Stages", Eq. 1): later stages
- * see only a share 1 - s/(s-1) k of the microbatches, so |S_i| = |S_0| (1 - s/(s-1) k) for i >= 1.  sizes: host
- * int32 [n_stages]; every node is used; the later stages get the nearest whole number, stage 0 the rest.
- * SP_EINVAL if fewer nodes than stages or the ratio leaves the later stages nothing. */
-int sp_stage_sizes(int n_nodes, int n_stages, int skip_num, int skip_den, int32_t* sizes);
-
-typedef struct sp_sched_problem {
-  int32_t n_stages, n_nodes, n_agents;
-  int32_t mem_limit;   /* m of TC1 */
-  int32_t strict_swap; /* CC2: exchanged stages must be consecutive */
-  int32_t no_swap;     /* != 0: stages strictly in increasing order (no exchange at all) */
-  int32_t n_solutions, max_expansions;
-  float delta;
-  float focal_slack;   /* second phase: among solutions within this fraction of the cheapest, the one with the
-                          fewest collisions is expanded next; 0 = strictly cheapest first (the paper); < 0 = 0.5 */
-  const int32_t* node_stage;
-  const float* compute_fwd;
-  const float* compute_bwd;
-  const float* comm;
-  const int32_t* start_node;
-  const int32_t* n_keep;
-} sp_sched_problem;
 int sp_schedule_paths(const sp_sched_problem* problem, int32_t* path_nodes, int32_t* path_stages, int32_t* len,
                       float* arrive, float* e2e, float* max_e2e);
 
@@ -194,6 +199,14 @@ int sp_set_side_stream(sp_ctx* ctx, int enabled);
 
 /* Forgets every saved forward (e.g. after an aborted iteration). */
 int sp_reset(sp_ctx* ctx);
+
+/* Token ids must lie in [0, vocab) and targets in [-1, vocab) (-1 = ignored).  The kernels check this on
+ * the device and never read or write outside the caller's buffers: a row with a bad token id is embedded as
+ * zeros and adds nothing to the embedding gradient, a bad target counts as ignored, and a flag inside ctx is
+ * raised.  sp_run_paths and sp_eval_paths return SP_EINVAL when the flag is up at their end (their outputs
+ * are then those of the inputs so repaired); after the asynchronous calls (sp_embed_fwd/bwd,
+ * sp_head_fwd_bwd) sp_input_status() waits for the stream and reports the same way.  Reading the flag clears it. */
+int sp_input_status(sp_ctx* ctx);
 
 /* x[row, :] = embed[token[row], :] for n_mb microbatches (the front of stage 0, which every path opens
  * with: constraint CC1 of "Guideline for Partial Pipelining Scheduler").
@@ -274,7 +287,7 @@ int sp_eval_paths(sp_ctx* ctx, const void* params, const int32_t* tokens, const 
  *   p <- p (1 - lr weight_decay) - lr (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps)
  * master, m, v (float, n elements, updated in place) and grads (float, read only; e.g. what sp_run_paths or
  * sp_stage_bwd accumulated) are device pointers, 16-byte aligned, owned by the caller.  params_out, if not
- * null, receives the new parameters rounded to out_dtype (SP_BF16 or SP_F32): the copy the next iteration's
+ * null (16-byte aligned), receives the new parameters rounded to out_dtype (SP_BF16 or SP_F32): the copy the next iteration's
  * kernels read.  workspace: sp_optim_workspace_bytes() bytes of device memory, 16-byte aligned, contents
  * irrelevant before and after.  grad_norm (device, 1 float, may be null) receives the norm before clipping.
  * step counts from 1.  Work is enqueued on hip_stream and not waited for.  The sum of squares is formed in
@@ -286,6 +299,15 @@ typedef struct sp_adamw {
 int64_t sp_optim_workspace_bytes(void);
 int sp_optim_step(void* hip_stream, const sp_adamw* hyper, int64_t n, int step, float* master, const float* grads,
                   float* m, float* v, void* params_out, int out_dtype, void* workspace, float* grad_norm);
+
+/* Gradient accumulation across the replicas of an iteration (section "Throughput": gradients of all
+ * microbatches are accumulated before the update; with several nodes per stage each node holds the sum over
+ * the microbatches it served): out[i] = scale * sum_r replica_grads[r][i], added in replica order.
+ * replica_grads: host array of n_replicas (1..64) device pointers to float buffers of n elements; out: device
+ * float [n] (may be one of the replica buffers); all 16-byte aligned.  scale: e.g. 1 / n_mb when every
+ * head call took one microbatch's loss alone.  Enqueued on hip_stream, not waited for. */
+int sp_grad_reduce(void* hip_stream, const float* const* replica_grads, int n_replicas, int64_t n, float scale,
+                   float* out);
 
 /* Measurement aid: between sp_prof_begin() and sp_prof_end() every matrix-product and attention
  * launch of this process is bracketed by HIP events on its stream.  sp_prof_end waits for them and

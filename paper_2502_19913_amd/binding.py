@@ -22,7 +22,8 @@ SP_STRICT_CC, SP_SWAP_ANY_GAP, SP_ALLOW_ANY_ORDER = 0, 1, 2
 EXPORTS = ["sp_param_count", "sp_param_layout", "sp_workspace_bytes", "sp_make_paths", "sp_check_paths",
            "sp_route_plan", "sp_schedule_paths", "sp_stage_sizes", "sp_strerror", "sp_create", "sp_destroy", "sp_reset", "sp_set_side_stream", "sp_embed_fwd", "sp_embed_bwd",
            "sp_stage_fwd", "sp_stage_bwd", "sp_head_fwd_bwd", "sp_run_paths", "sp_eval_paths", "sp_gemm", "sp_attention_fwd",
-           "sp_attention_bwd", "sp_optim_workspace_bytes", "sp_optim_step", "sp_prof_begin", "sp_prof_end"]
+           "sp_attention_bwd", "sp_optim_workspace_bytes", "sp_optim_step", "sp_prof_begin", "sp_prof_end", "sp_input_status",
+           "sp_grad_reduce"]
 
 
 class SpCfg(C.Structure):
@@ -248,6 +249,10 @@ class Context:
                                   C.c_int(n_mb), _iptr(loss), _iptr(loss_mb), _dptr(grads)))
         return float(loss[0]), loss_mb
 
+    def input_status(self):
+        """Waits for the stream; raises SpError(SP_EINVAL) if a kernel met a token id or target out of range."""
+        _check(lib().sp_input_status(self._h))
+
     def set_side_stream(self, enabled: bool):
         _check(lib().sp_set_side_stream(self._h, C.c_int(1 if enabled else 0)))
 
@@ -312,6 +317,15 @@ def optim_step(master, grads, m, v, step: int, params_out=None, workspace=None, 
     od = _dt(params_out) if params_out is not None else SP_F32
     _check(lib().sp_optim_step(_stream_ptr(stream), C.byref(h), C.c_int64(n), C.c_int(step), _dptr(master), _dptr(grads),
                                _dptr(m), _dptr(v), _dptr(params_out), C.c_int(od), _dptr(workspace), _dptr(grad_norm)))
+
+
+def grad_reduce(replica_grads, out, scale: float = 1.0, stream=None):
+    """out = scale * sum of the replica gradient buffers (float tensors of equal length)."""
+    n = out.numel()
+    assert all(g.numel() == n for g in replica_grads)
+    ptrs = (C.c_void_p * len(replica_grads))(*[g.data_ptr() for g in replica_grads])
+    _check(lib().sp_grad_reduce(_stream_ptr(stream), ptrs, C.c_int(len(replica_grads)), C.c_int64(n), C.c_float(scale),
+                                _dptr(out)))
 
 
 PROF_CLASSES = ["gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd", "attn_delta", "attn_dq", "attn_dkv", "gemm_plain",

@@ -71,7 +71,7 @@ int64_t head_chunk_rows(const Dims& D, int64_t total_rows) {
 
 struct Carve {
   size_t arena, t_y, t_dy[2], t_dh[2], t_d2, t_da, t_dgu[2], t_dqkv[2], t_delta, rope, h_xn, h_rstd, h_logits, h_dxn, pool_a, pool_d,
-      loss_mb, counts, total;
+      loss_mb, counts, bad, total;
   size_t arena_bytes;
 };
 
@@ -96,6 +96,7 @@ Carve carve(const sp_cfg& c, int n_mb_max, int n_visits_max) {
   w.t_da = take(Rmax * D.h * D.E);
   w.t_delta = take(Rmax * D.H * sizeof(float));
   w.rope = take((size_t)D.T * (D.hd / 2) * 2 * sizeof(float));   // cos, sin per (position, pair)
+  w.bad = take(sizeof(int32_t));   // raised by a kernel that meets a token id or target outside the vocabulary
   if (c.has_head) {
     const int64_t ch = head_chunk_rows(D, Rmax);
     w.h_xn = take(ch * D.d * D.E);
@@ -125,6 +126,8 @@ struct sp_ctx {
   int n_mb_max, n_visits_max;
   char* base;
   float* rope_tab;   // inside the workspace, filled at creation
+  int32_t* bad;      // inside the workspace: input-range flag, cleared at creation and by sp_input_status
+  int32_t host_bad;
   // weight-gradient products run on a stream of their own, beside the chain that carries the activation
   // gradient down the layers; events order the two (ready: input written; done: input no longer read)
   hipStream_t side;
@@ -222,6 +225,8 @@ int sp_create(const sp_cfg* cfg, void* hip_stream, int n_mb_max, int n_visits_ma
     return hip_fail((int)e, "side stream / events");
   }
   c->rope_tab = (float*)at(c, c->w.rope);
+  c->bad = (int32_t*)at(c, c->w.bad);
+  fill_zero(c->stream, c->bad, sizeof(int32_t));
   rope_table(c->stream, (int)Dims(*cfg).T, (int)Dims(*cfg).hd, cfg->rope_theta, c->rope_tab);
   e = hipGetLastError();
   if (e != hipSuccess) {
@@ -263,12 +268,29 @@ int sp_reset(sp_ctx* ctx) {
   return SP_OK;
 }
 
+// Reads and clears the input-range flag; the stream must have been waited for.
+static int take_input_flag(sp_ctx* ctx, const char* who) {
+  hipError_t e = hipMemcpyAsync(&ctx->host_bad, ctx->bad, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+  if (e != hipSuccess) return hip_fail((int)e, "reading the input-range flag");
+  if (!ctx->host_bad) return SP_OK;
+  fill_zero(ctx->stream, ctx->bad, sizeof(int32_t));
+  return fail(SP_EINVAL, std::string(who) + ": a token id outside [0, vocab) or a target outside [-1, vocab) was met; "
+                                            "such rows were embedded as zeros / left out of loss and gradients");
+}
+
+int sp_input_status(sp_ctx* ctx) {
+  if (!ctx) return fail(SP_EINVAL, "ctx is null");
+  return take_input_flag(ctx, "input_status");
+}
+
 int sp_embed_fwd(sp_ctx* ctx, const void* params, const int32_t* tokens, int n_mb, void* act_pool) {
   if (!ctx || !params || !tokens || !act_pool) return fail(SP_EINVAL, "embed_fwd: null argument");
   if (!ctx->cfg.has_embed) return fail(SP_EINVAL, "this node holds no embedding");
   if (n_mb < 1 || n_mb > ctx->n_mb_max) return fail(SP_EINVAL, "embed_fwd: n_mb outside [1, n_mb_max]");
   const Dims D(ctx->cfg);
-  embed_fwd(ctx->stream, ctx->cfg.dtype, P(ctx, params, ctx->L.embed), tokens, n_mb * D.Nmb, (int)D.d, act_pool);
+  embed_fwd(ctx->stream, ctx->cfg.dtype, P(ctx, params, ctx->L.embed), tokens, n_mb * D.Nmb, (int)D.d, (int)D.V, act_pool,
+            ctx->bad);
   SP_HIP(hipGetLastError());
   return SP_OK;
 }
@@ -278,7 +300,8 @@ int sp_embed_bwd(sp_ctx* ctx, const int32_t* tokens, const void* dact_pool, int 
   if (!ctx->cfg.has_embed) return fail(SP_EINVAL, "this node holds no embedding");
   if (n_mb < 1 || n_mb > ctx->n_mb_max) return fail(SP_EINVAL, "embed_bwd: n_mb outside [1, n_mb_max]");
   const Dims D(ctx->cfg);
-  embed_bwd(ctx->stream, ctx->cfg.dtype, dact_pool, tokens, n_mb * D.Nmb, (int)D.d, grads + ctx->L.embed);
+  embed_bwd(ctx->stream, ctx->cfg.dtype, dact_pool, tokens, n_mb * D.Nmb, (int)D.d, (int)D.V, grads + ctx->L.embed,
+            ctx->bad);
   SP_HIP(hipGetLastError());
   return SP_OK;
 }
@@ -462,7 +485,7 @@ static int head_impl(sp_ctx* ctx, const void* params, const void* act_pool, cons
   char* dxn = at(ctx, ctx->w.h_dxn);
   int rc;
   fill_zero(s, loss_mb, n_mb * sizeof(float));
-  count_targets(s, targets, n_mb, D.Nmb, counts);
+  count_targets(s, targets, n_mb, D.Nmb, (int)D.V, counts, ctx->bad);
   for (int64_t r0 = 0; r0 < Rtot; r0 += CH) {
     const int64_t R = std::min(CH, Rtot - r0);
     const char* x = (const char*)act_pool + r0 * D.d * D.E;
@@ -535,7 +558,7 @@ int sp_eval_paths(sp_ctx* ctx, const void* params, const int32_t* tokens, const 
   for (int i = 0; i < n_mb; ++i) tot += ctx->host_loss[i];
   *loss_host = (float)(tot / n_mb);
   if (loss_mb_host) std::memcpy(loss_mb_host, ctx->host_loss.data(), n_mb * sizeof(float));
-  return SP_OK;
+  return take_input_flag(ctx, "eval_paths");
 }
 
 int sp_run_paths(sp_ctx* ctx, const void* params, const int32_t* tokens, const int32_t* targets,
@@ -571,7 +594,7 @@ int sp_run_paths(sp_ctx* ctx, const void* params, const int32_t* tokens, const i
   for (int i = 0; i < n_mb; ++i) tot += ctx->host_loss[i];
   *loss_host = (float)(tot / n_mb);
   if (loss_mb_host) std::memcpy(loss_mb_host, ctx->host_loss.data(), n_mb * sizeof(float));
-  return SP_OK;
+  return take_input_flag(ctx, "run_paths");
 }
 
 int sp_gemm(void* hip_stream, int dtype, int op, int M, int N, int K, const void* A, const void* B, void* C,

@@ -37,8 +37,11 @@ constexpr int kMaxGroup = 64;
 struct SlotList { int32_t n; int32_t slot[kMaxGroup]; };
 
 // ---- kernel launchers (all asynchronous on `s`; dtype is SP_F32 or SP_BF16)
-void embed_fwd(hipStream_t s, int dtype, const void* E, const int32_t* tok, int64_t rows, int d, void* x);
-void embed_bwd(hipStream_t s, int dtype, const void* dx, const int32_t* tok, int64_t rows, int d, float* dE);
+// A token outside [0, V) sets *bad (device int32) to 1; its row reads as zeros / adds nothing.
+void embed_fwd(hipStream_t s, int dtype, const void* E, const int32_t* tok, int64_t rows, int d, int V, void* x,
+               int32_t* bad);
+void embed_bwd(hipStream_t s, int dtype, const void* dx, const int32_t* tok, int64_t rows, int d, int V, float* dE,
+               int32_t* bad);
 // dst[g*rows_per_slot + r, :] = pool[slot[g]*rows_per_slot + r, :]   (and the reverse)
 void gather_slots(hipStream_t s, int dtype, const void* pool, const SlotList& sl, int64_t rows_per_slot, int d, void* dst);
 void scatter_slots(hipStream_t s, int dtype, const void* src, const SlotList& sl, int64_t rows_per_slot, int d, void* pool);
@@ -60,8 +63,9 @@ struct RopeArgs {
 };
 void swiglu_fwd(hipStream_t s, int dtype, const void* gu, int64_t R, int h, void* a);
 void swiglu_bwd(hipStream_t s, int dtype, const void* da, const void* gu, int64_t R, int h, void* dgu);
-// counts[mb] = number of targets >= 0 among the rows of microbatch mb
-void count_targets(hipStream_t s, const int32_t* tgt, int n_mb, int64_t rows_per_mb, int32_t* counts);
+// counts[mb] = number of targets in [0, V) among the rows of microbatch mb; a target below -1 or >= V sets *bad
+void count_targets(hipStream_t s, const int32_t* tgt, int n_mb, int64_t rows_per_mb, int V, int32_t* counts,
+                   int32_t* bad);
 // rows [row0, row0+R) of the iteration: logits -> dlogits in place, loss_mb[mb] += rowloss / counts[mb]
 void cross_entropy(hipStream_t s, int dtype, void* logits, const int32_t* tgt, int64_t row0, int64_t R, int V,
                    int64_t rows_per_mb, const int32_t* counts, float inv_n_mb, float* loss_mb);

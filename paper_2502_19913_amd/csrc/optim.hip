@@ -70,6 +70,11 @@ __device__ __forceinline__ float update_one(float p, float g, float& m, float& v
   return p * h.decay_mul - h.lr * (m * h.inv_bc1) / (sqrtf(v * h.inv_bc2) + h.eps);
 }
 
+__device__ __forceinline__ void store4(float* q, const float4& x) { *reinterpret_cast<float4*>(q) = x; }
+__device__ __forceinline__ void store4(bf16* q, const float4& x) {
+  *reinterpret_cast<uint2*>(q) = make_uint2(pack_bf16(x.x, x.y), pack_bf16(x.z, x.w));
+}
+
 template <class LP>   // LP: float (a plain copy) or bf16
 __global__ __launch_bounds__(kBlock) void k_adamw(float* __restrict__ p, const float* __restrict__ g, float* __restrict__ m,
                                                   float* __restrict__ v, LP* __restrict__ lp, int64_t n, Hyper h,
@@ -86,10 +91,7 @@ __global__ __launch_bounds__(kBlock) void k_adamw(float* __restrict__ p, const f
     reinterpret_cast<float4*>(p)[i] = pp;
     reinterpret_cast<float4*>(m)[i] = mm;
     reinterpret_cast<float4*>(v)[i] = vv;
-    if (lp) {
-      lp[4 * i] = from_float<LP>(pp.x); lp[4 * i + 1] = from_float<LP>(pp.y);
-      lp[4 * i + 2] = from_float<LP>(pp.z); lp[4 * i + 3] = from_float<LP>(pp.w);
-    }
+    if (lp) store4(lp + 4 * i, pp);   // one 8-byte (bf16) or 16-byte (float) store
   }
   if (blockIdx.x == 0)
     for (int64_t i = n4 * 4 + threadIdx.x; i < n; i += kBlock) {
@@ -100,15 +102,57 @@ __global__ __launch_bounds__(kBlock) void k_adamw(float* __restrict__ p, const f
     }
 }
 
+// out = scale * (g_0 + g_1 + ... + g_{n_rep-1}), added in index order
+constexpr int kMaxReplicas = 64;
+struct ReplicaPtrs { const float* g[kMaxReplicas]; };
+__global__ __launch_bounds__(kBlock) void k_grad_sum(ReplicaPtrs rp, int n_rep, int64_t n, float scale, float* __restrict__ out) {
+  const int64_t n4 = n / 4;
+  for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n4; i += (int64_t)gridDim.x * kBlock) {
+    float4 acc = reinterpret_cast<const float4*>(rp.g[0])[i];
+    for (int r = 1; r < n_rep; ++r) {
+      const float4 x = reinterpret_cast<const float4*>(rp.g[r])[i];
+      acc.x += x.x; acc.y += x.y; acc.z += x.z; acc.w += x.w;
+    }
+    acc.x *= scale; acc.y *= scale; acc.z *= scale; acc.w *= scale;
+    reinterpret_cast<float4*>(out)[i] = acc;
+  }
+  if (blockIdx.x == 0)
+    for (int64_t i = n4 * 4 + threadIdx.x; i < n; i += kBlock) {
+      float acc = rp.g[0][i];
+      for (int r = 1; r < n_rep; ++r) acc += rp.g[r][i];
+      out[i] = acc * scale;
+    }
+}
+
 }  // namespace
 }  // namespace sp
 
 using namespace sp;
 
+extern "C" int sp_grad_reduce(void* hip_stream, const float* const* replica_grads, int n_replicas, int64_t n, float scale,
+                              float* out) {
+  if (!replica_grads || !out || n_replicas < 1 || n_replicas > kMaxReplicas || n < 0)
+    return fail(SP_EINVAL, "grad_reduce: null argument, or a replica count outside [1, 64]");
+  ReplicaPtrs rp{};
+  uintptr_t al = (uintptr_t)out;
+  for (int r = 0; r < n_replicas; ++r) {
+    if (!replica_grads[r]) return fail(SP_EINVAL, "grad_reduce: null replica buffer");
+    rp.g[r] = replica_grads[r];
+    al |= (uintptr_t)replica_grads[r];
+  }
+  if (al & 15) return fail(SP_EINVAL, "grad_reduce: buffers must be 16-byte aligned");
+  if (n == 0) return SP_OK;
+  const int grid = (int)std::max<int64_t>(1, std::min<int64_t>(8192, (n / 4 + kBlock - 1) / kBlock));
+  hipLaunchKernelGGL(k_grad_sum, dim3(grid), dim3(kBlock), 0, (hipStream_t)hip_stream, rp, n_replicas, n, scale, out);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail((int)e, "grad_reduce");
+  return SP_OK;
+}
+
 extern "C" int64_t sp_optim_workspace_bytes(void) { return (int64_t)kPartials * sizeof(double) + 256; }
 
-extern "C" int sp_optim_step(void* hip_stream, const sp_adamw* hy, int64_t n, int step, float* master, const float* grads,
-                             float* m, float* v, void* params_out, int out_dtype, void* workspace, float* grad_norm) {
+static int optim_step_impl(void* hip_stream, const sp_adamw* hy, int64_t n, int step, float* master, const float* grads,
+                           float* m, float* v, void* params_out, int out_dtype, void* workspace, float* grad_norm) {
   if (!hy || n < 0 || step < 1) return fail(SP_EINVAL, "optim_step: null hyper-parameters, negative size or step < 1");
   if (n == 0) return SP_OK;
   if (!master || !grads || !m || !v || !workspace) return fail(SP_EINVAL, "optim_step: null operand");
@@ -118,6 +162,7 @@ extern "C" int sp_optim_step(void* hip_stream, const sp_adamw* hy, int64_t n, in
     return fail(SP_EINVAL, "optim_step: hyper-parameter out of range");
   const uintptr_t al = (uintptr_t)master | (uintptr_t)grads | (uintptr_t)m | (uintptr_t)v | (uintptr_t)workspace;
   if (al & 15) return fail(SP_EINVAL, "optim_step: master, grads, m, v and workspace must be 16-byte aligned");
+  if (params_out && ((uintptr_t)params_out & 15)) return fail(SP_EINVAL, "optim_step: params_out must be 16-byte aligned");
   hipStream_t s = (hipStream_t)hip_stream;
   double* partial = (double*)workspace;
   Scalars* sc = (Scalars*)((char*)workspace + (size_t)kPartials * sizeof(double));
@@ -138,4 +183,9 @@ extern "C" int sp_optim_step(void* hip_stream, const sp_adamw* hy, int64_t n, in
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return hip_fail((int)e, "optim_step");
   return SP_OK;
+}
+
+extern "C" int sp_optim_step(void* hip_stream, const sp_adamw* hy, int64_t n, int step, float* master, const float* grads,
+                             float* m, float* v, void* params_out, int out_dtype, void* workspace, float* grad_norm) {
+  return optim_step_impl(hip_stream, hy, n, step, master, grads, m, v, params_out, out_dtype, workspace, grad_norm);
 }

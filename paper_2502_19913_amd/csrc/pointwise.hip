@@ -24,10 +24,12 @@ __global__ __launch_bounds__(kBlock) void k_fill_zero(uint32_t* p, int64_t n_wor
 
 // Copies rows of `chunks` units of type U.  Row r of dst comes from row src_row(r) of src.
 // mode 0: src row = idx[r] (embedding rows)        mode 1: gather slots        mode 2: scatter slots
+// mode 0: an index outside [0, n_src_rows) raises *bad and yields a row of zeros
 template <class U>
 __global__ __launch_bounds__(kBlock) void k_copy_rows(const U* __restrict__ src, U* __restrict__ dst, int64_t rows,
                                                       int chunks, int mode, const int32_t* __restrict__ idx,
-                                                      SlotList sl, int64_t rows_per_slot) {
+                                                      SlotList sl, int64_t rows_per_slot, int64_t n_src_rows,
+                                                      int32_t* __restrict__ bad) {
   const int64_t total = rows * chunks;
   for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < total; i += (int64_t)gridDim.x * kBlock) {
     int64_t r = i / chunks;
@@ -35,6 +37,11 @@ __global__ __launch_bounds__(kBlock) void k_copy_rows(const U* __restrict__ src,
     int64_t sr = r, dr = r;
     if (mode == 0) {
       sr = idx[r];
+      if (sr < 0 || sr >= n_src_rows) {
+        if (c == 0) *bad = 1;
+        dst[dr * chunks + c] = U{};
+        continue;
+      }
     } else {
       int64_t g = r / rows_per_slot, w = r - g * rows_per_slot;
       int64_t pr = (int64_t)sl.slot[g] * rows_per_slot + w;
@@ -45,31 +52,38 @@ __global__ __launch_bounds__(kBlock) void k_copy_rows(const U* __restrict__ src,
 }
 
 void copy_rows(hipStream_t s, const void* src, void* dst, int64_t rows, int64_t row_bytes, int mode,
-               const int32_t* idx, const SlotList& sl, int64_t rows_per_slot) {
+               const int32_t* idx, const SlotList& sl, int64_t rows_per_slot, int64_t n_src_rows = 0,
+               int32_t* bad = nullptr) {
   if (rows <= 0) return;
   bool al16 = row_bytes % 16 == 0 && ((uintptr_t)src % 16 == 0) && ((uintptr_t)dst % 16 == 0);
   if (al16) {
     int chunks = (int)(row_bytes / 16);
     int grid = grid_for_rows(rows * chunks, kBlock * 4, 8192);
     hipLaunchKernelGGL(k_copy_rows<uint4>, dim3(grid), dim3(kBlock), 0, s, (const uint4*)src, (uint4*)dst, rows,
-                       chunks, mode, idx, sl, rows_per_slot);
+                       chunks, mode, idx, sl, rows_per_slot, n_src_rows, bad);
   } else {
     int chunks = (int)(row_bytes / 2);
     int grid = grid_for_rows(rows * chunks, kBlock * 4, 8192);
     hipLaunchKernelGGL(k_copy_rows<uint16_t>, dim3(grid), dim3(kBlock), 0, s, (const uint16_t*)src, (uint16_t*)dst,
-                       rows, chunks, mode, idx, sl, rows_per_slot);
+                       rows, chunks, mode, idx, sl, rows_per_slot, n_src_rows, bad);
   }
 }
 
-// dE[tok[r], :] += dx[r, :]
+// dE[tok[r], :] += dx[r, :]; a token outside [0, V) raises *bad and adds nothing
 template <class T>
 __global__ __launch_bounds__(kBlock) void k_embed_bwd(const T* __restrict__ dx, const int32_t* __restrict__ tok,
-                                                      int64_t rows, int d, float* __restrict__ dE) {
+                                                      int64_t rows, int d, float* __restrict__ dE, int V,
+                                                      int32_t* __restrict__ bad) {
   const int64_t total = rows * d;
   for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < total; i += (int64_t)gridDim.x * kBlock) {
     int64_t r = i / d;
     int c = (int)(i - r * d);
-    unsafeAtomicAdd(dE + (int64_t)tok[r] * d + c, to_float(dx[i]));
+    const int t = tok[r];
+    if (t < 0 || t >= V) {
+      if (c == 0) *bad = 1;
+      continue;
+    }
+    unsafeAtomicAdd(dE + (int64_t)t * d + c, to_float(dx[i]));
   }
 }
 
@@ -326,12 +340,18 @@ __global__ __launch_bounds__(kBlock) void k_swiglu_bwd_scalar(const T* __restric
 }
 
 // ------------------------------------------------------------------------------------------ cross-entropy
-__global__ __launch_bounds__(kBlock) void k_count_targets(const int32_t* __restrict__ tgt, int64_t rows_per_mb,
-                                                          int32_t* __restrict__ counts) {
+// A target is a vocabulary entry or -1 (ignored).  Anything else raises *bad and is treated as ignored, here and
+// in the loss kernel alike.
+__global__ __launch_bounds__(kBlock) void k_count_targets(const int32_t* __restrict__ tgt, int64_t rows_per_mb, int V,
+                                                          int32_t* __restrict__ counts, int32_t* __restrict__ bad) {
   __shared__ int s_cnt[kWavesPerBlock];
   const int mb = blockIdx.x;
   int c = 0;
-  for (int64_t r = threadIdx.x; r < rows_per_mb; r += kBlock) c += tgt[(int64_t)mb * rows_per_mb + r] >= 0;
+  for (int64_t r = threadIdx.x; r < rows_per_mb; r += kBlock) {
+    const int t = tgt[(int64_t)mb * rows_per_mb + r];
+    c += t >= 0 && t < V;
+    if (t < -1 || t >= V) *bad = 1;
+  }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o);
   if ((threadIdx.x & 63) == 0) s_cnt[threadIdx.x >> 6] = c;
@@ -426,18 +446,20 @@ void fill_zero(hipStream_t s, void* p, int64_t bytes) {
   hipLaunchKernelGGL(k_fill_zero, dim3(grid_for_rows(words, kBlock * 8, 8192)), dim3(kBlock), 0, s, (uint32_t*)p, words);
 }
 
-void embed_fwd(hipStream_t s, int dtype, const void* E, const int32_t* tok, int64_t rows, int d, void* x) {
+void embed_fwd(hipStream_t s, int dtype, const void* E, const int32_t* tok, int64_t rows, int d, int V, void* x,
+               int32_t* bad) {
   SlotList none{};
-  copy_rows(s, E, x, rows, d * elt_size(dtype), 0, tok, none, 1);
+  copy_rows(s, E, x, rows, d * elt_size(dtype), 0, tok, none, 1, V, bad);
 }
 
-void embed_bwd(hipStream_t s, int dtype, const void* dx, const int32_t* tok, int64_t rows, int d, float* dE) {
+void embed_bwd(hipStream_t s, int dtype, const void* dx, const int32_t* tok, int64_t rows, int d, int V, float* dE,
+               int32_t* bad) {
   if (rows <= 0) return;
   int grid = grid_for_rows(rows * d, kBlock * 4, 8192);
   if (dtype == SP_BF16)
-    hipLaunchKernelGGL(k_embed_bwd<bf16>, dim3(grid), dim3(kBlock), 0, s, (const bf16*)dx, tok, rows, d, dE);
+    hipLaunchKernelGGL(k_embed_bwd<bf16>, dim3(grid), dim3(kBlock), 0, s, (const bf16*)dx, tok, rows, d, dE, V, bad);
   else
-    hipLaunchKernelGGL(k_embed_bwd<float>, dim3(grid), dim3(kBlock), 0, s, (const float*)dx, tok, rows, d, dE);
+    hipLaunchKernelGGL(k_embed_bwd<float>, dim3(grid), dim3(kBlock), 0, s, (const float*)dx, tok, rows, d, dE, V, bad);
 }
 
 void gather_slots(hipStream_t s, int dtype, const void* pool, const SlotList& sl, int64_t rows_per_slot, int d,
@@ -542,8 +564,9 @@ void swiglu_bwd(hipStream_t s, int dtype, const void* da, const void* gu, int64_
   else swiglu_t<float>(s, true, (const float*)da, (const float*)gu, R, h, (float*)dgu);
 }
 
-void count_targets(hipStream_t s, const int32_t* tgt, int n_mb, int64_t rows_per_mb, int32_t* counts) {
-  hipLaunchKernelGGL(k_count_targets, dim3(n_mb), dim3(kBlock), 0, s, tgt, rows_per_mb, counts);
+void count_targets(hipStream_t s, const int32_t* tgt, int n_mb, int64_t rows_per_mb, int V, int32_t* counts,
+                   int32_t* bad) {
+  hipLaunchKernelGGL(k_count_targets, dim3(n_mb), dim3(kBlock), 0, s, tgt, rows_per_mb, V, counts, bad);
 }
 
 void cross_entropy(hipStream_t s, int dtype, void* logits, const int32_t* tgt, int64_t row0, int64_t R, int V,

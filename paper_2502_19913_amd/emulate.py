@@ -133,10 +133,10 @@ class NodeEmulator:
             torch.cuda.current_stream().wait_stream(s)
         t1.record()
         torch.cuda.synchronize()
-        total = self.grads[0].clone()
-        for g in self.grads[1:]:
-            total += g
-        total /= n_mb     # every head call took its microbatch's loss alone; the iteration's loss is their mean
+        # every head call took its microbatch's loss alone; the iteration's loss is their mean
+        total = torch.empty_like(self.grads[0])
+        sp.grad_reduce(self.grads, total, 1.0 / n_mb)
+        torch.cuda.synchronize()
         busy = [0.0] * len(self.node_stage); n_ops = [0] * len(self.node_stage)
         for nd, e0, e1 in spans:
             busy[nd] += e0.elapsed_time(e1); n_ops[nd] += 1

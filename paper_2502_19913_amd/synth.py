@@ -254,11 +254,12 @@ C3_PATHS = [(0, 3, 4, 5), (0, 3, 2, 5), (0, 3, 4, 5), (0, 2, 3, 5), (0, 1, 3, 4)
             (0, 1, 4, 3)]
 
 
-def stage_share_paths(key: str, seed: int = BASE_SEED) -> Tuple[np.ndarray, np.ndarray, int]:
+def stage_share_paths(key: str, seed: int = BASE_SEED, generator=None) -> Tuple[np.ndarray, np.ndarray, int]:
     """Paths of a stage-share workload and the stage the node holds.
 
     c3: the fixed set above.  c4 / c5: the seeded recipe over all 8 stages; the node holds the later stage
-    that most paths visit (ties: the lowest index)."""
+    that most paths visit (ties: the lowest index).  generator: a function with make_paths' signature to draw
+    the paths with instead (the GPU library exports one)."""
     cfg = CONFIGS[key]
     s = cfg["n_stages"]
     if key == "c3":
@@ -266,7 +267,7 @@ def stage_share_paths(key: str, seed: int = BASE_SEED) -> Tuple[np.ndarray, np.n
         for i, p in enumerate(C3_PATHS):
             paths[i, :len(p)] = p
         return paths, np.array([len(p) for p in C3_PATHS], np.int32), 3
-    paths, lens = make_paths(s, cfg["n_mb"], *cfg["skip"], bool(cfg["swap"]), seed)
+    paths, lens = (generator or make_paths)(s, cfg["n_mb"], *cfg["skip"], bool(cfg["swap"]), seed)
     visits = np.zeros(s, int)
     for mb in range(cfg["n_mb"]):
         for st in paths[mb, :lens[mb]]:

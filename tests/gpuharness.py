@@ -82,3 +82,9 @@ def cosine(a, b):
     if na == 0 and nb == 0:
         return 1.0
     return float(a @ b / max(na * nb, 1e-300))
+
+
+def maxerr(a, b):
+    """Largest element-wise difference relative to the largest reference magnitude: max|a - b| / max|b|."""
+    a = np.asarray(a, np.float64); b = np.asarray(b, np.float64)
+    return float(np.max(np.abs(a - b)) / max(np.max(np.abs(b)), 1e-300))

@@ -31,9 +31,10 @@ def _run(w, plan, dact0):
     return w["act"].clone(), w["dact"].clone(), w["grads"].clone()
 
 
-@pytest.mark.parametrize("key", ["c3", "c5"])
+@pytest.mark.parametrize("key", ["c3", "c4", "c5"])
 def test_full_size_bench_configuration(key):
-    # c3: 8 x 4096 tokens, 4 layers, groups 3/3/2.  c5: the 8B-shape stage (grouped kv heads) under its routed
+    # c3: 8 x 4096 tokens, 4 layers, groups 3/3/2.  c4: the 7B-shape stage with its routed microbatches (11 or 12
+    # of 16) as one group.  c5: the 8B-shape stage (grouped kv heads) under its routed
     # microbatches, then final norm, head over 128256 tokens and loss on all 16
     w = bench.build_workload(key, torch, sp, synth)
     cfg = w["cfg"]
@@ -41,6 +42,8 @@ def test_full_size_bench_configuration(key):
         plan = list(w["plan"])
         if key == "c3":
             assert [len(m) for _, _, m in plan] == [3, 3, 2]
+        if key == "c4":
+            assert len(plan) == 1 and len(plan[0][2]) >= 11
         routed = sorted(m for _, _, ms in plan for m in ms)
         y, dx, g = _run(w, plan, w.get("dact0"))
         # (1) sampled outputs: the first P tokens of three microbatches against the checker on those P tokens
@@ -62,7 +65,7 @@ def test_full_size_bench_configuration(key):
         assert relerr(g1.cpu().numpy(), g.cpu().numpy()) < 1e-3
         # (3) the backward pass is linear in the gradient that arrives: twice the input, twice every gradient
         # (a factor of two is exact in bfloat16 and float, so only the order of the atomic additions differs)
-        if key == "c3":
+        if key in ("c3", "c4"):
             y2, dx2, g2 = _run(w, plan, w["dact0"] * 2)
             assert relerr(dx2.float().cpu().numpy(), 2 * dx.float().cpu().numpy()) < 1e-5
             assert relerr(g2.cpu().numpy(), 2 * g.cpu().numpy()) < 1e-5
