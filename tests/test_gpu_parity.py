@@ -325,7 +325,7 @@ def test_out_of_range_token_ids_and_targets_are_reported_not_followed():
     finally:
         ctx.close()
     again = run(cfg, named, full, lens, tokens=tok, targets=tgt)       # a clean run afterwards is unaffected
-    assert again["loss"] == clean["loss"]
+    assert math.isclose(again["loss"], clean["loss"], rel_tol=1e-6)      # float atomics: the order of additions varies
 
 
 def test_side_stream_changes_nothing_but_the_order_of_float_additions():
