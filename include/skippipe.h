@@ -300,6 +300,18 @@ int64_t sp_optim_workspace_bytes(void);
 int sp_optim_step(void* hip_stream, const sp_adamw* hyper, int64_t n, int step, float* master, const float* grads,
                   float* m, float* v, void* params_out, int out_dtype, void* workspace, float* grad_norm);
 
+/* sp_optim_step for callers that cannot allocate or pass a workspace: code under HIP graph capture, tight
+ * serving / training loops, harnesses that forbid hipMalloc.  Same arguments without `workspace`, same kernels,
+ * same results bit for bit.  The norm partials and clip factor (16 640 bytes) live in a static device array of
+ * the library instead; every GPU the library runs on holds its own copy until the process ends.  The call
+ * allocates nothing (no hipMalloc / hipFree, no allocating library routine); the array's address on the
+ * current device is looked up on the first call on that device.  Nothing in the array has to start at zero
+ * (every partial that is read was written by the same call).  All calls on one GPU share the array: two calls
+ * that overlap in time on one GPU (different streams, different threads) race and give wrong norms; calls on one
+ * stream, or otherwise ordered, are fine.  SP_EINVAL also if n exceeds 2^32 elements. */
+int sp_optim_step_noalloc(void* hip_stream, const sp_adamw* hyper, int64_t n, int step, float* master,
+                          const float* grads, float* m, float* v, void* params_out, int out_dtype, float* grad_norm);
+
 /* Gradient accumulation across the replicas of an iteration (section "Throughput": gradients of all
  * microbatches are accumulated before the update; with several nodes per stage each node holds the sum over
  * the microbatches it served): out[i] = scale * sum_r replica_grads[r][i], added in replica order.

@@ -23,7 +23,7 @@ EXPORTS = ["sp_param_count", "sp_param_layout", "sp_workspace_bytes", "sp_make_p
            "sp_route_plan", "sp_schedule_paths", "sp_stage_sizes", "sp_strerror", "sp_create", "sp_destroy", "sp_reset", "sp_set_side_stream", "sp_embed_fwd", "sp_embed_bwd",
            "sp_stage_fwd", "sp_stage_bwd", "sp_head_fwd_bwd", "sp_run_paths", "sp_eval_paths", "sp_gemm", "sp_attention_fwd",
            "sp_attention_bwd", "sp_optim_workspace_bytes", "sp_optim_step", "sp_prof_begin", "sp_prof_end", "sp_input_status",
-           "sp_grad_reduce"]
+           "sp_grad_reduce", "sp_optim_step_noalloc"]
 
 
 class SpCfg(C.Structure):
@@ -317,6 +317,16 @@ def optim_step(master, grads, m, v, step: int, params_out=None, workspace=None, 
     od = _dt(params_out) if params_out is not None else SP_F32
     _check(lib().sp_optim_step(_stream_ptr(stream), C.byref(h), C.c_int64(n), C.c_int(step), _dptr(master), _dptr(grads),
                                _dptr(m), _dptr(v), _dptr(params_out), C.c_int(od), _dptr(workspace), _dptr(grad_norm)))
+
+
+def optim_step_noalloc(master, grads, m, v, step: int, params_out=None, grad_norm=None, lr=3e-4, beta1=0.9, beta2=0.999,
+                       eps=1e-8, weight_decay=0.01, clip_norm=1.0, stream=None):
+    """optim_step without a workspace argument: the library's static device scratch is used; allocates nothing."""
+    h = SpAdamW(lr, beta1, beta2, eps, weight_decay, clip_norm)
+    od = _dt(params_out) if params_out is not None else SP_F32
+    _check(lib().sp_optim_step_noalloc(_stream_ptr(stream), C.byref(h), C.c_int64(master.numel()), C.c_int(step),
+                                       _dptr(master), _dptr(grads), _dptr(m), _dptr(v), _dptr(params_out), C.c_int(od),
+                                       _dptr(grad_norm)))
 
 
 def grad_reduce(replica_grads, out, scale: float = 1.0, stream=None):

@@ -8,6 +8,8 @@
 //   pass 2  one workgroup adds the partials in index order: norm, and the factor min(1, clip/(norm+1e-6))
 //   pass 3  m, v, master parameter and its low-precision copy in one sweep: 4 floats per lane per access.
 // HBM traffic per parameter: 4 (norm) + 16 read + 12 written + 2 (bf16 copy) = 34 bytes.
+#include <mutex>
+
 #include "devutil.h"
 #include "internal.h"
 
@@ -188,4 +190,40 @@ static int optim_step_impl(void* hip_stream, const sp_adamw* hy, int64_t n, int 
 extern "C" int sp_optim_step(void* hip_stream, const sp_adamw* hy, int64_t n, int step, float* master, const float* grads,
                              float* m, float* v, void* params_out, int out_dtype, void* workspace, float* grad_norm) {
   return optim_step_impl(hip_stream, hy, n, step, master, grads, m, v, params_out, out_dtype, workspace, grad_norm);
+}
+
+// ---- the same update for callers that must not allocate: the norm partials and the two scalars live in a
+// file-scope device array instead of a caller-provided workspace.  Each GPU the library runs on holds its own
+// copy of the array (at its own address) from the moment the code object is loaded until the process ends.
+namespace {
+constexpr size_t kScratchBytes = (size_t)kPartials * sizeof(double) + 256;   // 16 640 bytes
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+constexpr int kMaxDevices = 64;
+void* g_scratch_addr[kMaxDevices];   // device address of `scratch` per device, looked up once
+std::mutex g_scratch_mutex;
+constexpr int64_t kNoAllocMaxN = (int64_t)1 << 32;
+}  // namespace
+
+extern "C" int sp_optim_step_noalloc(void* hip_stream, const sp_adamw* hy, int64_t n, int step, float* master,
+                                     const float* grads, float* m, float* v, void* params_out, int out_dtype,
+                                     float* grad_norm) {
+  if (n > kNoAllocMaxN)
+    return fail(SP_EINVAL, "optim_step_noalloc: n = " + std::to_string(n) + " exceeds the maximum of 2^32 elements per call");
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail((int)e, "hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices) return fail(SP_EINVAL, "optim_step_noalloc: device index outside [0, 64)");
+  void* ptr = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_addr[dev]) {
+      // in host code the array's name is only a handle: this is the address the kernels may use, on this device
+      void* p = nullptr;
+      e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+      if (e != hipSuccess || !p) return hip_fail((int)e, "hipGetSymbolAddress(scratch)");
+      g_scratch_addr[dev] = p;
+    }
+    ptr = g_scratch_addr[dev];
+  }
+  return optim_step_impl(hip_stream, hy, n, step, master, grads, m, v, params_out, out_dtype, ptr, grad_norm);
 }
