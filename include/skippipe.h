@@ -257,6 +257,16 @@ int sp_run_paths(sp_ctx* ctx, const void* params, const int32_t* tokens, const i
 int sp_gemm(void* hip_stream, int dtype, int op, int M, int N, int K, const void* A, const void* B, void* C,
             const void* R);
 
+/* The two feed-forward steps whose pointwise part rides in a matrix product's epilogue (the SwiGLU block of the
+ * decoder layer: act = silu(gate) * up with [gate | up] = hn wgu^T, and its gradient), exposed for unit tests.
+ *   sp_ffn_up_fwd:   gu[R, 2h] = hn[R, d] * wgu[2h, d]^T  and  act[R, h] = silu(gu[:, :h]) * gu[:, h:]
+ *   sp_ffn_down_bwd: dgu[R, 2h] = d(gate) | d(up) for d(act) = dy[R, d] * wd[d, h] and the saved gu;
+ *                    da_scratch [R, h] is used only where the fused kernel does not apply (float, odd shapes)
+ * All tensors in dtype, row-major, dense. */
+int sp_ffn_up_fwd(void* hip_stream, int dtype, int R, int h, int d, const void* hn, const void* wgu, void* gu, void* act);
+int sp_ffn_down_bwd(void* hip_stream, int dtype, int R, int h, int d, const void* dy, const void* wd, const void* gu,
+                    void* dgu, void* da_scratch);
+
 /* Causal softmax attention with grouped kv heads as used by the stages (per sequence and head:
  * softmax(q k^T / sqrt(hd) + causal mask) v, and its gradients), exposed for unit tests and roofline
  * measurement.

@@ -23,7 +23,7 @@ EXPORTS = ["sp_param_count", "sp_param_layout", "sp_workspace_bytes", "sp_make_p
            "sp_route_plan", "sp_schedule_paths", "sp_stage_sizes", "sp_strerror", "sp_create", "sp_destroy", "sp_reset", "sp_set_side_stream", "sp_embed_fwd", "sp_embed_bwd",
            "sp_stage_fwd", "sp_stage_bwd", "sp_head_fwd_bwd", "sp_run_paths", "sp_eval_paths", "sp_gemm", "sp_attention_fwd",
            "sp_attention_bwd", "sp_optim_workspace_bytes", "sp_optim_step", "sp_prof_begin", "sp_prof_end", "sp_input_status",
-           "sp_grad_reduce", "sp_optim_step_noalloc"]
+           "sp_grad_reduce", "sp_optim_step_noalloc", "sp_ffn_up_fwd", "sp_ffn_down_bwd"]
 
 
 class SpCfg(C.Structure):
@@ -289,6 +289,20 @@ def gemm(op: int, A, B, C_out, R=None, stream=None):
         K, M = A.shape; N = B.shape[1]
     _check(lib().sp_gemm(_stream_ptr(stream), C.c_int(_dt(A)), C.c_int(op), C.c_int(M), C.c_int(N), C.c_int(K),
                          _dptr(A), _dptr(B), _dptr(C_out), _dptr(R)))
+
+
+def ffn_up_fwd(hn, wgu, gu, act, stream=None):
+    """gu = hn wgu^T and act = silu(gate) * up in one call."""
+    R, d = hn.shape; h = act.shape[1]
+    _check(lib().sp_ffn_up_fwd(_stream_ptr(stream), C.c_int(_dt(hn)), C.c_int(R), C.c_int(h), C.c_int(d), _dptr(hn),
+                               _dptr(wgu), _dptr(gu), _dptr(act)))
+
+
+def ffn_down_bwd(dy, wd, gu, dgu, da_scratch, stream=None):
+    """dgu = gradient of [gate | up] for d(act) = dy wd and the saved gu."""
+    R, d = dy.shape; h = wd.shape[1]
+    _check(lib().sp_ffn_down_bwd(_stream_ptr(stream), C.c_int(_dt(dy)), C.c_int(R), C.c_int(h), C.c_int(d), _dptr(dy),
+                                 _dptr(wd), _dptr(gu), _dptr(dgu), _dptr(da_scratch)))
 
 
 def attention_fwd(qkv, o, lse, B, T, H, Hkv, hd, stream=None):

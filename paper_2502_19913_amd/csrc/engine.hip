@@ -356,8 +356,7 @@ static int stage_fwd_impl(sp_ctx* ctx, int stage, const void* params, void* act_
     if ((rc = attention_fwd(s, dt, Bg, (int)D.T, (int)D.H, (int)D.Hkv, (int)D.hd, ls.qkv, ls.o, ls.lse))) return rc;
     if ((rc = gemm(s, dt, 0, R, D.d, D.d, ls.o, P(ctx, params, w.wo), ls.h, ls.x))) return rc;
     rmsnorm_fwd(s, dt, ls.h, P(ctx, params, w.g2), R, (int)D.d, cfg.rms_eps, ls.hn, ls.rstd2);
-    if ((rc = gemm(s, dt, 0, R, 2 * D.h, D.d, ls.hn, P(ctx, params, w.wgu), ls.gu, nullptr))) return rc;
-    swiglu_fwd(s, dt, ls.gu, R, (int)D.h, ls.a);
+    if ((rc = ffn_up_fwd(s, dt, R, D.h, D.d, ls.hn, P(ctx, params, w.wgu), ls.gu, ls.a))) return rc;
     if ((rc = gemm(s, dt, 0, R, D.d, D.h, ls.a, P(ctx, params, w.wd), y, ls.h))) return rc;
   }
   scatter_slots(s, dt, at(ctx, ctx->w.t_y), sl, D.Nmb, (int)D.d, act_pool);
@@ -433,9 +432,8 @@ int sp_stage_bwd(sp_ctx* ctx, int stage, const void* params, void* dact_pool, co
     char* dqkv = at(ctx, ctx->w.t_dqkv[par]);
     // feed-forward: y = h + a Wd^T
     if ((rc = side_dw(0, par, D.d, D.h, dy, ls.a, grads + w.wd))) return rc;
-    if ((rc = gemm(s, dt, 1, R, D.h, D.d, dy, P(ctx, params, w.wd), da, nullptr))) return rc;
     if ((rc = wait_done(1, par))) return rc;
-    swiglu_bwd(s, dt, da, ls.gu, R, (int)D.h, dgu);
+    if ((rc = ffn_down_bwd(s, dt, R, D.h, D.d, dy, P(ctx, params, w.wd), ls.gu, dgu, da))) return rc;
     if ((rc = side_dw(1, par, 2 * D.h, D.d, dgu, ls.hn, grads + w.wgu))) return rc;
     if ((rc = gemm(s, dt, 1, R, D.d, 2 * D.h, dgu, P(ctx, params, w.wgu), t, nullptr))) return rc;
     if ((rc = wait_done(2, par))) return rc;
@@ -601,6 +599,23 @@ int sp_gemm(void* hip_stream, int dtype, int op, int M, int N, int K, const void
             const void* R) {
   if (dtype != SP_F32 && dtype != SP_BF16) return fail(SP_EINVAL, "gemm: unknown dtype");
   int rc = gemm((hipStream_t)hip_stream, dtype, op, M, N, K, A, B, C, R);
+  if (rc) return rc;
+  SP_HIP(hipGetLastError());
+  return SP_OK;
+}
+
+int sp_ffn_up_fwd(void* hip_stream, int dtype, int R, int h, int d, const void* hn, const void* wgu, void* gu, void* act) {
+  if (dtype != SP_F32 && dtype != SP_BF16) return fail(SP_EINVAL, "ffn: unknown dtype");
+  int rc = ffn_up_fwd((hipStream_t)hip_stream, dtype, R, h, d, hn, wgu, gu, act);
+  if (rc) return rc;
+  SP_HIP(hipGetLastError());
+  return SP_OK;
+}
+
+int sp_ffn_down_bwd(void* hip_stream, int dtype, int R, int h, int d, const void* dy, const void* wd, const void* gu,
+                    void* dgu, void* da_scratch) {
+  if (dtype != SP_F32 && dtype != SP_BF16) return fail(SP_EINVAL, "ffn: unknown dtype");
+  int rc = ffn_down_bwd((hipStream_t)hip_stream, dtype, R, h, d, dy, wd, gu, dgu, da_scratch);
   if (rc) return rc;
   SP_HIP(hipGetLastError());
   return SP_OK;

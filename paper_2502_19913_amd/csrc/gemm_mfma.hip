@@ -65,8 +65,10 @@ constexpr uint32_t kPastEnd = 0x80000000u;      // no descriptor is this large
 // Byte offset, from the tile's first row (k-contiguous) or first x (k-strided) at the step's first k, of the
 // 16-byte chunk that belongs at position q of the tile in LDS (layouts above); kc8: for k-contiguous tiles, the
 // first k of that chunk inside the step.
+// split (k-contiguous only): the second half of the tile's rows lies `split` rows further on in memory (the gate
+// and up rows of a SwiGLU projection that share one tile).
 template <bool KSTRIDED, bool W32, int TILE>
-__device__ __forceinline__ uint32_t chunk_offset(int q, int ld, int& kc8) {
+__device__ __forceinline__ uint32_t chunk_offset(int q, int ld, int& kc8, int split = 0) {
   constexpr int XCH = Geo<TILE>::XCH;
   if (KSTRIDED) {
     const int krow = q / XCH, pos = q % XCH;
@@ -75,7 +77,7 @@ __device__ __forceinline__ uint32_t chunk_offset(int q, int ld, int& kc8) {
   }
   const int row = q >> 3, pos = q & 7, c = pos ^ ((row >> 1) & 7);
   kc8 = c * 8;
-  return ((uint32_t)row * ld + c * 8) * 2u;
+  return ((uint32_t)(row + (row >= TILE / 2 ? split : 0)) * ld + c * 8) * 2u;
 }
 
 // One operand's share of the tile loads for one wavefront: TILE / 64 instructions of 1 KiB per step.
@@ -98,7 +100,7 @@ struct Operand {
   int kc8;             // k-contiguous: first k of the lane's chunk inside a step
   // rows x ld elements in memory; origin: first tile row (k-contiguous) or first x (k-strided).
   // Offsets stay below 2^31 for ld < 2^21 (checked by the caller); the operand itself may be larger.
-  __device__ __forceinline__ void init(const bf16* X, int64_t rows, int ld, int origin, int wave, int lane) {
+  __device__ __forceinline__ void init(const bf16* X, int64_t rows, int ld, int origin, int wave, int lane, int split = 0) {
     const int64_t first = KSTRIDED ? (int64_t)origin : (int64_t)origin * ld;
     base = reinterpret_cast<const char*>(X + first);
     left = (rows * ld - first) * 2;
@@ -106,7 +108,7 @@ struct Operand {
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
       const int q = (8 * j + wave) * 64 + lane;
-      voff[j] = chunk_offset<KSTRIDED, W32, TILE>(q, ld, kc8);   // kc8: the same for every j (lane and wave & 1 only)
+      voff[j] = chunk_offset<KSTRIDED, W32, TILE>(q, ld, kc8, split);   // kc8: the same for every j (lane and wave & 1 only)
     }
     k_step = KSTRIDED ? (uint32_t)ld * 2u : 2u;
   }
@@ -137,7 +139,7 @@ struct HalfLoader {
   int kc8;
   bool strided;
   __device__ __forceinline__ void init(bool late, const bf16* A, int64_t a_rows, int a_ld, int a_origin, const bf16* B,
-                                       int64_t b_rows, int b_ld, int b_origin, int w4, int lane) {
+                                       int64_t b_rows, int b_ld, int b_origin, int w4, int lane, int b_split = 0) {
     const bf16* X = late ? B : A;
     const int64_t rows = late ? b_rows : a_rows;
     const int ld = late ? b_ld : a_ld, origin = late ? b_origin : a_origin;
@@ -150,9 +152,10 @@ struct HalfLoader {
     for (int j = 0; j < NJ; ++j) {
       const int q = (4 * j + w4) * 64 + lane;
       int kc_a = 0, kc_b = 0;
-      const uint32_t oa = chunk_offset<AS, W32, TILE>(q, ld, kc_a), ob = AS == BS ? oa : chunk_offset<BS, W32, TILE>(q, ld, kc_b);
+      const uint32_t oa = chunk_offset<AS, W32, TILE>(q, ld, kc_a);
+      const uint32_t ob = (AS == BS && b_split == 0) ? oa : chunk_offset<BS, W32, TILE>(q, ld, kc_b, b_split);
       voff[j] = late ? ob : oa;
-      kc8 = late ? (AS == BS ? kc_a : kc_b) : kc_a;
+      kc8 = late ? ((AS == BS && b_split == 0) ? kc_a : kc_b) : kc_a;
     }
     k_step = strided ? (uint32_t)ld * 2u : 2u;
   }
@@ -220,11 +223,29 @@ __device__ __forceinline__ bf16x8 read_frag32(const char* tile, int row_base, in
   }
 }
 
-// ROPE (op 0 only): the leading rope.rot_cols columns of the output are rotated on the way out
-template <int OP, bool KMASK, bool ROPE, int TILE, bool PP = false>
+// What happens to a bf16 output tile on its way out (EPI):
+//   kEpiPlain      stored, plus the matrix R if given (op 0)
+//   kEpiRope       op 0: the leading rope.rot_cols columns are rotated
+//   kEpiSwiglu     op 0, N = 2h, B = [gate rows | up rows]: a tile holds TILE/2 gate columns and the TILE/2 up
+//                  columns of the same features (tiles_n = h / (TILE/2)); C receives both at their places and
+//                  aux[M, h] receives silu(gate) * up, formed from the rounded values C holds
+//   kEpiSwigluBwd  op 1, N = h: the product is d(act); with gate|up read from R[M, 2h], C[M, 2h] receives
+//                  d(gate) | d(up); d(act) itself is not stored
+enum { kEpiPlain = 0, kEpiRope = 1, kEpiSwiglu = 2, kEpiSwigluBwd = 3 };
+
+__device__ __forceinline__ void unpack8(const uint4& v, float (&x)[8]) {
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int e = 0; e < 4; ++e) { x[2 * e] = bf16_bits_to_float(w[e] & 0xffffu); x[2 * e + 1] = bf16_bits_to_float(w[e] >> 16); }
+}
+
+template <int OP, bool KMASK, int EPI, int TILE, bool PP = false>
 __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ B,
                                                         void* __restrict__ Cv, const bf16* __restrict__ Rr, int M,
-                                                        int N, int K, int tiles_m, int tiles_n, RopeArgs rope) {
+                                                        int N, int K, int tiles_m, int tiles_n, RopeArgs rope,
+                                                        bf16* __restrict__ aux) {
+  constexpr bool ROPE = EPI == kEpiRope;
+  static_assert(EPI == kEpiPlain || (EPI == kEpiSwigluBwd ? OP == 1 : OP == 0), "epilogue and product do not match");
   constexpr bool AS = OP == 2, BS = OP != 0;   // which operands are k-strided
   typedef Geo<TILE> G;
   constexpr int kTileBytes = G::kTileBytes, kStageBytes = G::kStageBytes, kCRowBytes = G::kCRowBytes;
@@ -258,7 +279,10 @@ __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__
   const int band_w = min(kBand, tiles_n - band * kBand);
   const int in_band = tile - band * kBand * tiles_m;
   const int tm = in_band / band_w, tn = band * kBand + in_band % band_w;
-  const int m0 = tm * BM, n0 = tn * BN;
+  // n0: first output column of the tile (kEpiSwiglu: first gate column; the up columns start at hN + n0)
+  const int hN = N / 2;
+  const int m0 = tm * BM, n0 = EPI == kEpiSwiglu ? tn * (BN / 2) : tn * BN;
+  const int b_split = EPI == kEpiSwiglu ? hN - BN / 2 : 0;
   const int kb = ks0 * BK, kend = min(K, ks1 * BK);
   const int nk = ks1 - ks0;
 
@@ -266,7 +290,7 @@ __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__
   Operand<AS, W32, TILE> opa;
   Operand<BS, W32, TILE> opb;
   opa.init(A, AS ? K : M, AS ? M : K, m0, wave, lane);
-  opb.init(B, BS ? K : N, BS ? N : K, n0, wave, lane);
+  opb.init(B, BS ? K : N, BS ? N : K, n0, wave, lane, b_split);
 
   // OP 0/1: acc[j][i] = 16 output rows m x 16 output columns n of the wavefront's WM x WN share.
   // OP 2: acc32[j][i] = 32 rows x 32 columns of it.
@@ -359,7 +383,7 @@ __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__
     char* const a_ring = smem;                       // 2 tiles
     char* const b_ring = smem + 2 * kTileBytes;      // 3 tiles
     HalfLoader<AS, BS, W32, TILE> mine;
-    mine.init(late, A, AS ? K : M, AS ? M : K, m0, B, BS ? K : N, BS ? N : K, n0, w4, lane);
+    mine.init(late, A, AS ? K : M, AS ? M : K, m0, B, BS ? K : N, BS ? N : K, n0, w4, lane, b_split);
     auto issue_a = [&](int t) { mine.template load<KMASK>(kb + t * BK, kend, a_ring + (t & 1) * kTileBytes, w4); };
     auto issue_b = [&](int t, int slot) { mine.template load<KMASK>(kb + t * BK, kend, b_ring + slot * kTileBytes, w4); };
     if (!late) issue_a(0);
@@ -467,6 +491,49 @@ __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__
     __syncthreads();
     bf16* C = reinterpret_cast<bf16*>(Cv);
     const bool add = OP == 0 && Rr != nullptr;
+    if (EPI == kEpiSwiglu) {
+      // chunk nc < TILE/16 of a staged row is 8 gate values, chunk nc + TILE/16 the up values of the same features
+#pragma unroll 4
+      for (int it = 0; it < TILE * TILE / 16 / kThreads; ++it) {
+        const int c = tid + kThreads * it;
+        const int row = c / (TILE / 16), nc = c % (TILE / 16);
+        const int grow = m0 + row, gcol = n0 + nc * 8;
+        if (grow < M) {
+          const uint4 vg = *reinterpret_cast<const uint4*>(smem + row * kCRowBytes + nc * 16);
+          const uint4 vu = *reinterpret_cast<const uint4*>(smem + row * kCRowBytes + (nc + TILE / 16) * 16);
+          float g[8], u[8], o[8];
+          unpack8(vg, g);
+          unpack8(vu, u);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) o[e] = g[e] / (1.0f + expf(-g[e])) * u[e];
+          *reinterpret_cast<uint4*>(C + (int64_t)grow * N + gcol) = vg;
+          *reinterpret_cast<uint4*>(C + (int64_t)grow * N + hN + gcol) = vu;
+          store8(aux + (int64_t)grow * hN + gcol, o);
+        }
+      }
+    } else if (EPI == kEpiSwigluBwd) {
+#pragma unroll 4
+      for (int it = 0; it < TILE * TILE / 8 / kThreads; ++it) {
+        const int c = tid + kThreads * it;
+        const int row = c / (TILE / 8), nc = c % (TILE / 8);
+        const int grow = m0 + row, gcol = n0 + nc * 8;
+        if (grow < M && gcol < N) {
+          float d[8], g[8], u[8], og[8], ou[8];
+          unpack8(*reinterpret_cast<const uint4*>(smem + row * kCRowBytes + nc * 16), d);
+          const int64_t at = (int64_t)grow * 2 * N + gcol;
+          load8(Rr + at, g);
+          load8(Rr + at + N, u);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const float sg = 1.0f / (1.0f + expf(-g[e]));
+            og[e] = d[e] * u[e] * sg * (1.0f + g[e] * (1.0f - sg));
+            ou[e] = d[e] * g[e] * sg;
+          }
+          store8(C + at, og);
+          store8(C + at + N, ou);
+        }
+      }
+    } else
 #pragma unroll 4
     for (int it = 0; it < TILE * TILE / 8 / kThreads; ++it) {
       const int c = tid + kThreads * it;
@@ -541,16 +608,22 @@ bool gemm_mfma_supported(int op, int64_t M, int64_t N, int64_t K, const void* A,
   return false;
 }
 
+// epi: kEpiPlain (R optional), kEpiRope (rope given), kEpiSwiglu (N = 2h, aux = act out), kEpiSwigluBwd (N = h,
+// R = gate|up in, C = d(gate)|d(up) out)
 void gemm_mfma(hipStream_t s, int op, int64_t M, int64_t N, int64_t K, const void* A, const void* B, void* C,
-               const void* R, const RopeArgs* rope) {
+               const void* R, const RopeArgs* rope, int epi, void* aux) {
+  if (rope) epi = kEpiRope;
   // The chip delivers about the same aggregate rate with two thirds of its CUs busy as with all of them
   // (the kernel is bound by what the L2s and the power budget give), but a nearly empty round is lost time.
   const int cus = cu_count();
   // 256 x 256 tiles move the fewest bytes per flop; a product with too few of them to occupy the CUs
   // (a single microbatch through a narrow layer) takes 128 x 128 tiles instead
   const int64_t big = ((M + 255) / 256) * ((N + 255) / 256);
-  const int tile = (op != 2 && big * 4 < (int64_t)cus * 3) ? 128 : 256;
-  const int tm = (int)((M + tile - 1) / tile), tn = (int)((N + tile - 1) / tile);
+  int tile = (op != 2 && big * 4 < (int64_t)cus * 3) ? 128 : 256;
+  if (epi == kEpiSwiglu && (N / 2) % 128) tile = 128;   // the caller has checked (N/2) % 64 == 0
+  const int tm = (int)((M + tile - 1) / tile);
+  // kEpiSwiglu: a tile covers tile/2 gate and the matching tile/2 up columns
+  const int tn = epi == kEpiSwiglu ? (int)(N / tile) : (int)((N + tile - 1) / tile);
   const int tiles = tm * tn;
   int wgs;
   if (op == 2) {
@@ -576,16 +649,36 @@ void gemm_mfma(hipStream_t s, int op, int64_t M, int64_t N, int64_t K, const voi
   const bf16* r = (const bf16*)R;
   const bool kmask = K % BK != 0;
   const RopeArgs ra = rope ? *rope : RopeArgs{nullptr, 1, 8, 0};
-#define SP_LAUNCH(OP, KM, RP, TL) \
-  hipLaunchKernelGGL((k_gemm_mfma<OP, KM, RP, TL, TL == 256>), grid, dim3(kThreads), 0, s, a, b, C, r, (int)M, (int)N, (int)K, tm, tn, ra)
-#define SP_LAUNCH_T(OP, KM, RP) \
-  do { if (tile == 128) SP_LAUNCH(OP, KM, RP, 128); else SP_LAUNCH(OP, KM, RP, 256); } while (0)
-  if (op == 0 && rope) { if (kmask) SP_LAUNCH_T(0, true, true); else SP_LAUNCH_T(0, false, true); }
-  else if (op == 0) { if (kmask) SP_LAUNCH_T(0, true, false); else SP_LAUNCH_T(0, false, false); }
-  else if (op == 1) { if (kmask) SP_LAUNCH_T(1, true, false); else SP_LAUNCH_T(1, false, false); }
-  else SP_LAUNCH(2, false, false, 256);
+#define SP_LAUNCH(OP, KM, EP, TL) \
+  hipLaunchKernelGGL((k_gemm_mfma<OP, KM, EP, TL, TL == 256>), grid, dim3(kThreads), 0, s, a, b, C, r, (int)M, (int)N, (int)K, tm, tn, ra, (bf16*)aux)
+#define SP_LAUNCH_K(OP, EP, TL) \
+  do { if (kmask) SP_LAUNCH(OP, true, EP, TL); else SP_LAUNCH(OP, false, EP, TL); } while (0)
+#define SP_LAUNCH_T(OP, EP) \
+  do { if (tile == 128) SP_LAUNCH_K(OP, EP, 128); else SP_LAUNCH_K(OP, EP, 256); } while (0)
+  if (op == 0 && epi == kEpiRope) SP_LAUNCH_T(0, kEpiRope);
+  else if (op == 0 && epi == kEpiSwiglu) SP_LAUNCH_T(0, kEpiSwiglu);
+  else if (op == 0) SP_LAUNCH_T(0, kEpiPlain);
+  else if (op == 1 && epi == kEpiSwigluBwd) SP_LAUNCH_T(1, kEpiSwigluBwd);
+  else if (op == 1) SP_LAUNCH_T(1, kEpiPlain);
+  else SP_LAUNCH(2, false, kEpiPlain, 256);
 #undef SP_LAUNCH_T
+#undef SP_LAUNCH_K
 #undef SP_LAUNCH
+}
+
+bool gemm_swiglu_supported(bool bwd, int64_t R, int64_t h, int64_t d, const void* X, const void* W, const void* gu,
+                           const void* other) {
+  if (h % 64) return false;   // forward: a tile of 128 or 256 columns holds whole halves of gate and up
+  if (bwd) return gemm_mfma_supported(1, R, h, d, X, W, other, gu);
+  return gemm_mfma_supported(0, R, 2 * h, d, X, W, gu, other);
+}
+
+void gemm_mfma_swiglu_fwd(hipStream_t s, int64_t R, int64_t h, int64_t d, const void* hn, const void* wgu, void* gu, void* act) {
+  gemm_mfma(s, 0, R, 2 * h, d, hn, wgu, gu, nullptr, nullptr, kEpiSwiglu, act);
+}
+
+void gemm_mfma_swiglu_bwd(hipStream_t s, int64_t R, int64_t h, int64_t d, const void* dy, const void* wd, const void* gu, void* dgu) {
+  gemm_mfma(s, 1, R, h, d, dy, wd, dgu, gu, nullptr, kEpiSwigluBwd, nullptr);
 }
 
 }  // namespace sp

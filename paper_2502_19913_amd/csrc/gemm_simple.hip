@@ -123,4 +123,37 @@ int gemm_rope(hipStream_t s, int dtype, int64_t M, int64_t N, int64_t K, const v
   return SP_OK;
 }
 
+int ffn_up_fwd(hipStream_t s, int dtype, int64_t R, int64_t h, int64_t d, const void* hn, const void* wgu, void* gu, void* act) {
+  if (R < 0 || h < 1 || d < 1) return fail(SP_EINVAL, "ffn_up_fwd: bad shape");
+  if (R == 0) return SP_OK;
+  if (!hn || !wgu || !gu || !act) return fail(SP_EINVAL, "ffn_up_fwd: null operand");
+  if (dtype == SP_BF16 && gemm_swiglu_supported(false, R, h, d, hn, wgu, gu, act)) {
+    const int pi = prof_start(0, s);
+    gemm_mfma_swiglu_fwd(s, R, h, d, hn, wgu, gu, act);
+    prof_stop(pi, s, 4.0 * (double)R * (double)h * (double)d);
+    return SP_OK;
+  }
+  int rc = gemm(s, dtype, 0, R, 2 * h, d, hn, wgu, gu, nullptr);
+  if (rc) return rc;
+  swiglu_fwd(s, dtype, gu, R, (int)h, act);
+  return SP_OK;
+}
+
+int ffn_down_bwd(hipStream_t s, int dtype, int64_t R, int64_t h, int64_t d, const void* dy, const void* wd, const void* gu,
+                 void* dgu, void* da_tmp) {
+  if (R < 0 || h < 1 || d < 1) return fail(SP_EINVAL, "ffn_down_bwd: bad shape");
+  if (R == 0) return SP_OK;
+  if (!dy || !wd || !gu || !dgu || !da_tmp) return fail(SP_EINVAL, "ffn_down_bwd: null operand");
+  if (dtype == SP_BF16 && gemm_swiglu_supported(true, R, h, d, dy, wd, gu, dgu)) {
+    const int pi = prof_start(1, s);
+    gemm_mfma_swiglu_bwd(s, R, h, d, dy, wd, gu, dgu);
+    prof_stop(pi, s, 2.0 * (double)R * (double)h * (double)d);
+    return SP_OK;
+  }
+  int rc = gemm(s, dtype, 1, R, h, d, dy, wd, da_tmp, nullptr);
+  if (rc) return rc;
+  swiglu_bwd(s, dtype, da_tmp, gu, R, (int)h, dgu);
+  return SP_OK;
+}
+
 }  // namespace sp

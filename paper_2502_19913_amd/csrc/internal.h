@@ -90,7 +90,19 @@ void gemm_simple(hipStream_t s, int dtype, int op, int64_t M, int64_t N, int64_t
 bool gemm_mfma_supported(int op, int64_t M, int64_t N, int64_t K, const void* A, const void* B, const void* C,
                          const void* R);
 void gemm_mfma(hipStream_t s, int op, int64_t M, int64_t N, int64_t K, const void* A, const void* B, void* C,
-               const void* R, const RopeArgs* rope = nullptr);
+               const void* R, const RopeArgs* rope = nullptr, int epi = 0, void* aux = nullptr);
+// the feed-forward projections with the SwiGLU arithmetic in their epilogues (bf16, matrix cores):
+//   forward   gu[R, 2h] = hn[R, d] wgu[2h, d]^T  and  act[R, h] = silu(gate) * up
+//   backward  dgu[R, 2h] = swiglu'(dy[R, d] wd[d, h]; gu)            (d(act) is never stored)
+bool gemm_swiglu_supported(bool bwd, int64_t R, int64_t h, int64_t d, const void* X, const void* W, const void* gu,
+                           const void* other);
+void gemm_mfma_swiglu_fwd(hipStream_t s, int64_t R, int64_t h, int64_t d, const void* hn, const void* wgu, void* gu, void* act);
+void gemm_mfma_swiglu_bwd(hipStream_t s, int64_t R, int64_t h, int64_t d, const void* dy, const void* wd, const void* gu, void* dgu);
+// the same two steps whatever the dtype and shape: fused where the matrix-core path takes them, else the plain
+// product with the pointwise kernel after it; da_tmp [R, h]: scratch for the unfused backward path
+int ffn_up_fwd(hipStream_t s, int dtype, int64_t R, int64_t h, int64_t d, const void* hn, const void* wgu, void* gu, void* act);
+int ffn_down_bwd(hipStream_t s, int dtype, int64_t R, int64_t h, int64_t d, const void* dy, const void* wd, const void* gu,
+                 void* dgu, void* da_tmp);
 void attention_simple_fwd(hipStream_t s, int dtype, int B, int T, int H, int Hkv, int hd, const void* qkv, void* o,
                           float* lse);
 void attention_simple_bwd(hipStream_t s, int dtype, int B, int T, int H, int Hkv, int hd, const void* qkv,

@@ -7,7 +7,7 @@ import torch
 from oracle import skippipe_oracle as orc
 from paper_2502_19913_amd import binding as sp
 from paper_2502_19913_amd import synth
-from tests.gpuharness import cosine, relerr, round_bf16
+from tests.gpuharness import cosine, maxerr, relerr, round_bf16
 
 pytestmark = pytest.mark.gpu
 
@@ -91,6 +91,39 @@ def test_gemm_operand_larger_than_2gib():
     _, ref2 = orc.linear_bwd(big[:, cols].float().cpu().numpy().astype(np.float64), d.astype(np.float64),
                              np.zeros((len(cols), N)))
     assert relerr(c2[cols].cpu().numpy(), ref2) < 2e-5
+
+
+FFN_SHAPES = [  # R, h, d: tiles of 256 (h % 128 == 0) and of 128 (h % 64 == 0), ragged rows, ragged reduction,
+    (1000, 1280, 264),      # and shapes the fused kernels do not take (h % 64 != 0)
+    (4096, 2816, 1024), (300, 192, 72), (5000, 1152, 520), (77, 96, 40), (2560, 5632, 128), (3000, 5632, 200),
+]
+
+
+@pytest.mark.parametrize("R,h,d", FFN_SHAPES)
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_feed_forward_steps_with_swiglu_in_the_epilogue(R, h, d, dtype):
+    dt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    rnd = round_bf16 if dtype == "bf16" else (lambda a: a)
+    tol = 6e-3 if dtype == "bf16" else 3e-5
+    hn = rnd(synth.normal(11, f"hn{R}{h}{d}", (R, d)))
+    wgu = rnd(synth.normal(12, f"wgu{R}{h}{d}", (2 * h, d), std=2.0 / np.sqrt(d)))
+    gu_ref = orc.linear_fwd(hn.astype(np.float64), wgu.astype(np.float64))
+    gu = torch.full((R, 2 * h), 9.0, dtype=dt, device="cuda"); act = torch.full((R, h), 9.0, dtype=dt, device="cuda")
+    sp.ffn_up_fwd(dev(hn, dt), dev(wgu, dt), gu, act)
+    gu_got = gu.float().cpu().numpy()
+    assert relerr(gu_got, gu_ref) < tol
+    # act is formed from the gu the kernel stored (rounded in bf16 mode): one more rounding on the way out
+    assert relerr(act.float().cpu().numpy(), orc.swiglu_fwd(gu_got.astype(np.float64))) < (4e-3 if dtype == "bf16" else 1e-5)
+    # backward: d(act) = dy wd, then the SwiGLU gradient against the saved gu
+    dy = rnd(synth.normal(13, f"dy{R}{h}{d}", (R, d)))
+    wd = rnd(synth.normal(14, f"wd{R}{h}{d}", (d, h), std=1.0 / np.sqrt(d)))
+    da_ref = dy.astype(np.float64) @ wd.astype(np.float64)
+    dgu_ref = orc.swiglu_bwd(da_ref, gu_got.astype(np.float64))
+    dgu = torch.full((R, 2 * h), 9.0, dtype=dt, device="cuda"); scratch = torch.empty((R, h), dtype=dt, device="cuda")
+    sp.ffn_down_bwd(dev(dy, dt), dev(wd, dt), gu, dgu, scratch)
+    got = dgu.float().cpu().numpy()
+    assert relerr(got, dgu_ref) < (8e-3 if dtype == "bf16" else 3e-5), relerr(got, dgu_ref)
+    assert maxerr(got, dgu_ref) < (3e-2 if dtype == "bf16" else 1e-4)
 
 
 def test_gemm_rejects_bad_arguments():
