@@ -68,11 +68,20 @@ __device__ __forceinline__ bf16x8 read_tr(const char* tile, int RS, int col_base
 }
 
 // Workgroups are dealt to the 8 XCDs (each with its own L2) in turn: linear id L runs on XCD L % 8.
-// This renumbering of 0..N-1 gives every XCD one contiguous range, so that workgroups with neighbouring
-// numbers, which here share the K/V (or Q/dO) rows they stream, meet in one L2.
-__device__ __forceinline__ int xcd_major(int L, int N) {
-  const int per = N / 8, rem = N % 8, x = L % 8;
-  return x * per + min(x, rem) + L / 8;
+// Longest blocks first over the whole launch: linear id L -> (level, sequence, head) with the level (which
+// query or key block of the causal triangle, i.e. how much work) changing slowest, so the heaviest blocks of
+// all heads start first and the light ones fill the tail (a launch has a few blocks per CU and their costs differ
+// by the number of blocks of the triangle's side).  Within a level, ids that land on one XCD get neighbouring
+// heads (the query heads of one kv group when the head count is a multiple of 8): the K/V (or Q/dO) rows a
+// head streams are then re-read, level after level, through the same L2.
+struct BlockId { int level, b, a; };
+__device__ __forceinline__ BlockId heavy_first(int L, int B, int H) {
+  const int per_level = B * H, level = L / per_level, j = L - level * per_level;
+  if (H % 8 == 0) {
+    const int g = j % 8, r = j / 8, hx = H / 8;
+    return {level, r / hx, g * hx + r % hx};
+  }
+  return {level, j / H, j % H};
 }
 
 // Gradient of a rotated vector -> gradient of the vector before the rotation, for 4 consecutive columns
@@ -137,9 +146,9 @@ __global__ __launch_bounds__(256, 2) void k_flash_fwd(const bf16* __restrict__ q
   constexpr int kKTile = BKV * KS, kVTile = BKV * VS;
   __shared__ __attribute__((aligned(16))) char smem[2 * (kKTile + kVTile)];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lq = lane & 31, hh = lane >> 5;
-  // heaviest query blocks first; the blocks of a head, then the heads of a sequence, are numbered together
-  const int nqb = (T + 127) / 128, wg = xcd_major(blockIdx.x, gridDim.x);
-  const int qb = nqb - 1 - wg % nqb, a = (wg / nqb) % H, b = wg / (nqb * H);
+  const int nqb = (T + 127) / 128;
+  const BlockId id = heavy_first(blockIdx.x, (int)gridDim.x / (nqb * H), H);   // heaviest query blocks first
+  const int qb = nqb - 1 - id.level, a = id.a, b = id.b;
   const int kvh = a / (H / Hkv);
   const int64_t ld = (int64_t)(H + 2 * Hkv) * HD;
   const bf16* Q = qkv + (int64_t)b * T * ld + a * HD;
@@ -322,9 +331,9 @@ __global__ __launch_bounds__(256, 2) void k_flash_bwd_dq(const bf16* __restrict_
   constexpr int kKTile = BKV * KS, kTTile = BKV * TS;
   __shared__ __attribute__((aligned(16))) char smem[2 * kKTile + kTTile];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lq = lane & 31, hh = lane >> 5;
-  // heaviest query blocks first; the blocks of a head, then the heads of a sequence, are numbered together
-  const int nqb = (T + 127) / 128, wg = xcd_major(blockIdx.x, gridDim.x);
-  const int qb = nqb - 1 - wg % nqb, a = (wg / nqb) % H, b = wg / (nqb * H);
+  const int nqb = (T + 127) / 128;
+  const BlockId id = heavy_first(blockIdx.x, (int)gridDim.x / (nqb * H), H);   // heaviest query blocks first
+  const int qb = nqb - 1 - id.level, a = id.a, b = id.b;
   const int kvh = a / (H / Hkv);
   const int64_t ld = (int64_t)(H + 2 * Hkv) * HD;
   const bf16* Q = qkv + (int64_t)b * T * ld + a * HD;
@@ -500,9 +509,9 @@ __global__ __launch_bounds__(256) void k_flash_bwd_dkv(const bf16* __restrict__ 
   __shared__ __attribute__((aligned(1024))) char smem[kRing * kBuf];
   const int tid = threadIdx.x, lane = tid & 63, lk = lane & 31, hh = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  // heaviest key blocks (the first) first; the blocks of a kv head are numbered together
-  const int nkb = (T + BK - 1) / BK, wg = xcd_major(blockIdx.x, gridDim.x);
-  const int kb = wg % nkb, kvh = (wg / nkb) % Hkv, b = wg / (nkb * Hkv);
+  const int nkb = (T + BK - 1) / BK;
+  const BlockId id = heavy_first(blockIdx.x, (int)gridDim.x / (nkb * Hkv), Hkv);   // heaviest key blocks (the first) first
+  const int kb = id.level, kvh = id.a, b = id.b;
   const int rep = H / Hkv;
   const int64_t ld = (int64_t)(H + 2 * Hkv) * HD;
   const bf16* Kp = qkv + (int64_t)b * T * ld + (H + kvh) * HD;
