@@ -506,9 +506,9 @@ __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__
           unpack8(vu, u);
 #pragma unroll
           for (int e = 0; e < 8; ++e) o[e] = g[e] / (1.0f + expf(-g[e])) * u[e];
-          *reinterpret_cast<uint4*>(C + (int64_t)grow * N + gcol) = vg;
-          *reinterpret_cast<uint4*>(C + (int64_t)grow * N + hN + gcol) = vu;
-          store8(aux + (int64_t)grow * hN + gcol, o);
+          store16_stream(C + (int64_t)grow * N + gcol, vg);
+          store16_stream(C + (int64_t)grow * N + hN + gcol, vu);
+          store8_stream(aux + (int64_t)grow * hN + gcol, o);
         }
       }
     } else if (EPI == kEpiSwigluBwd) {
@@ -529,8 +529,8 @@ __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__
             og[e] = d[e] * u[e] * sg * (1.0f + g[e] * (1.0f - sg));
             ou[e] = d[e] * g[e] * sg;
           }
-          store8(C + at, og);
-          store8(C + at + N, ou);
+          store8_stream(C + at, og);
+          store8_stream(C + at + N, ou);
         }
       }
     } else
@@ -557,7 +557,7 @@ __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__
             x[2 * e] = a * c[e] - b * sn[e];
             x[2 * e + 1] = a * sn[e] + b * c[e];
           }
-          store8(C + at, x);
+          store8_stream(C + at, x);
         } else if (add) {
           // the sum is formed in float from the accumulator's bf16 rounding; one more rounding on the way out
           float x[8], y[8];
@@ -567,9 +567,9 @@ __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__
           load8(Rr + at, y);
 #pragma unroll
           for (int e = 0; e < 8; ++e) x[e] += y[e];
-          store8(C + at, x);
+          store8_stream(C + at, x);
         } else {
-          *reinterpret_cast<uint4*>(C + at) = v;
+          store16_stream(C + at, v);
         }
       }
     }
