@@ -62,8 +62,10 @@ size_t layer_saved_bytes(const Dims& D, int64_t rows) {
   return b;
 }
 
+// Rows of logits materialised at a time.  Every chunk adds its share of the head's weight gradient into the float
+// gradient buffer (vocab x dim x 4 bytes read and written per chunk), so chunks are made large: up to 8 GiB of logits.
 int64_t head_chunk_rows(const Dims& D, int64_t total_rows) {
-  int64_t ch = ((int64_t)1 << 30) / std::max<int64_t>(1, D.V * D.E);
+  int64_t ch = ((int64_t)8 << 30) / std::max<int64_t>(1, D.V * D.E);
   ch = ch / 256 * 256;
   if (ch < 256) ch = 256;
   return std::min(ch, total_rows);
