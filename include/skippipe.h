@@ -227,7 +227,7 @@ int sp_stage_fwd(sp_ctx* ctx, int stage, const void* params, void* act_pool, con
  * microbatches are summed before any update ("System Setting").
  * Backward of the same group (same stage, same mb_idx in the same order; SP_ESTATE otherwise):
  * dact_pool slots hold dL/d(output) on entry and dL/d(input) on return; parameter gradients are
- * added into grads (float, parameter layout). */
+ * added into grads (float, parameter layout) with float atomics. */
 int sp_stage_bwd(sp_ctx* ctx, int stage, const void* params, void* dact_pool, const int32_t* mb_idx, int n_group,
                  float* grads);
 

@@ -73,7 +73,7 @@ int64_t head_chunk_rows(const Dims& D, int64_t total_rows) {
 
 struct Carve {
   size_t arena, t_y, t_dy[2], t_dh[2], t_d2, t_da, t_dgu[2], t_dqkv[2], t_delta, rope, h_xn, h_rstd, h_logits, h_dxn, pool_a, pool_d,
-      loss_mb, counts, bad, total;
+      loss_mb, counts, bad, dgpart, total;
   size_t arena_bytes;
 };
 
@@ -98,6 +98,7 @@ Carve carve(const sp_cfg& c, int n_mb_max, int n_visits_max) {
   w.t_da = take(Rmax * D.h * D.E);
   w.t_delta = take(Rmax * D.H * sizeof(float));
   w.rope = take((size_t)D.T * (D.hd / 2) * 2 * sizeof(float));   // cos, sin per (position, pair)
+  w.dgpart = take((size_t)kRmsPartRows * D.d * sizeof(float));   // per-block partial sums of a norm's gain gradient
   w.bad = take(sizeof(int32_t));   // raised by a kernel that meets a token id or target outside the vocabulary
   if (c.has_head) {
     const int64_t ch = head_chunk_rows(D, Rmax);
@@ -403,6 +404,8 @@ int sp_stage_bwd(sp_ctx* ctx, int stage, const void* params, void* dact_pool, co
   char* t = at(ctx, ctx->w.t_d2);
   char* da = at(ctx, ctx->w.t_da);
   float* delta = (float*)at(ctx, ctx->w.t_delta);
+  float* dgpart = (float*)at(ctx, ctx->w.dgpart);
+  const int64_t dgpart_n = (int64_t)kRmsPartRows * D.d;
   hipStream_t side = ctx->use_side ? ctx->side : s;
   for (int p = 0; p < 2; ++p)
     for (int i = 0; i < 4; ++i) ctx->done_set[p][i] = false;
@@ -439,7 +442,7 @@ int sp_stage_bwd(sp_ctx* ctx, int stage, const void* params, void* dact_pool, co
     if ((rc = side_dw(1, par, 2 * D.h, D.d, dgu, ls.hn, grads + w.wgu))) return rc;
     if ((rc = gemm(s, dt, 1, R, D.d, 2 * D.h, dgu, P(ctx, params, w.wgu), t, nullptr))) return rc;
     if ((rc = wait_done(2, par))) return rc;
-    rmsnorm_bwd(s, dt, t, ls.h, P(ctx, params, w.g2), ls.rstd2, dy, R, (int)D.d, dh, grads + w.g2);
+    rmsnorm_bwd(s, dt, t, ls.h, P(ctx, params, w.g2), ls.rstd2, dy, R, (int)D.d, dh, grads + w.g2, dgpart, dgpart_n);
     // attention: h = x + o Wo^T
     if ((rc = side_dw(2, par, D.d, D.d, dh, ls.o, grads + w.wo))) return rc;
     if ((rc = gemm(s, dt, 1, R, D.d, D.d, dh, P(ctx, params, w.wo), t, nullptr))) return rc;
@@ -450,7 +453,7 @@ int sp_stage_bwd(sp_ctx* ctx, int stage, const void* params, void* dact_pool, co
     if ((rc = side_dw(3, par, D.nq, D.d, dqkv, ls.xn, grads + w.wqkv))) return rc;
     if ((rc = gemm(s, dt, 1, R, D.d, D.nq, dqkv, P(ctx, params, w.wqkv), t, nullptr))) return rc;
     if ((rc = wait_done(0, par ^ 1))) return rc;   // the layer above may still read its dy
-    rmsnorm_bwd(s, dt, t, ls.x, P(ctx, params, w.g1), ls.rstd1, dh, R, (int)D.d, dy_next, grads + w.g1);
+    rmsnorm_bwd(s, dt, t, ls.x, P(ctx, params, w.g1), ls.rstd1, dh, R, (int)D.d, dy_next, grads + w.g1, dgpart, dgpart_n);
   }
   char* dy = at(ctx, ctx->w.t_dy[par]);
   // the caller's stream continues only after every weight gradient has landed
@@ -496,7 +499,8 @@ static int head_impl(sp_ctx* ctx, const void* params, const void* act_pool, cons
     if (!backward) continue;
     if ((rc = gemm(s, dt, 2, D.V, D.d, R, logits, xn, grads + ctx->L.whead, nullptr))) return rc;
     if ((rc = gemm(s, dt, 1, R, D.d, D.V, logits, P(ctx, params, ctx->L.whead), dxn, nullptr))) return rc;
-    rmsnorm_bwd(s, dt, dxn, x, P(ctx, params, ctx->L.gf), rstd, nullptr, R, (int)D.d, dx, grads + ctx->L.gf);
+    rmsnorm_bwd(s, dt, dxn, x, P(ctx, params, ctx->L.gf), rstd, nullptr, R, (int)D.d, dx, grads + ctx->L.gf,
+                (float*)at(ctx, ctx->w.dgpart), (int64_t)kRmsPartRows * D.d);
   }
   SP_HIP(hipGetLastError());
   return SP_OK;

@@ -49,8 +49,11 @@ void fill_zero(hipStream_t s, void* p, int64_t bytes);
 
 void rmsnorm_fwd(hipStream_t s, int dtype, const void* x, const void* g, int64_t R, int d, float eps, void* y, float* rstd);
 // dx = (dres ? dres : 0) + rmsnorm'(dy) ; dg += sum_rows dy * x * rstd
+// part (may be null): scratch of part_floats floats for the per-block partial sums of dg (kRmsPartRows x d is
+// enough), which a second kernel adds up
+constexpr int kRmsPartRows = 1024;
 void rmsnorm_bwd(hipStream_t s, int dtype, const void* dy, const void* x, const void* g, const float* rstd,
-                 const void* dres, int64_t R, int d, void* dx, float* dg);
+                 const void* dres, int64_t R, int d, void* dx, float* dg, float* part = nullptr, int64_t part_floats = 0);
 // rotates the first nheads*hd columns of every row (row_stride elements apart); position = row % T
 void rope(hipStream_t s, int dtype, void* qk, int64_t R, int T, int nheads, int hd, int row_stride, float theta, int sign);
 // table[(p * hd/2 + i) * 2 + {0, 1}] = cos, sin of p * theta^(-2i/hd), the angles rope() uses, for p < T

@@ -141,12 +141,15 @@ __global__ __launch_bounds__(kBlock) void k_rmsnorm_fwd_scalar(const T* __restri
 
 // xh = x*rstd ; dxh = dy*g ; dx = rstd*(dxh - xh*mean(dxh*xh)) (+ dres) ; dg += sum_rows dy*xh.
 // Each lane keeps the dg partial sums of its columns over all rows its wavefront visits; the block
-// folds its four wavefronts in LDS and issues one atomic add per column.
+// folds its four wavefronts in LDS and hands one value per column on: into its own row of part_out when that is
+// given (a second kernel adds the rows up: hundreds of blocks adding atomically into the same d addresses
+// queue up at a few L2 channels and cost more than the rows' traffic), else as one atomic add per column.
 template <class T, int NV>
 __global__ __launch_bounds__(kBlock) void k_rmsnorm_bwd(const T* __restrict__ dy, const T* __restrict__ x,
                                                         const T* __restrict__ g, const float* __restrict__ rstd,
                                                         const T* __restrict__ dres, int64_t R, int d,
-                                                        T* __restrict__ dx, float* __restrict__ dg) {
+                                                        T* __restrict__ dx, float* __restrict__ dg,
+                                                        float* __restrict__ part_out) {
   extern __shared__ float s_dg[];
   const int lane = threadIdx.x & 63;
   const int64_t nw = (int64_t)gridDim.x * kWavesPerBlock;
@@ -211,8 +214,30 @@ __global__ __launch_bounds__(kBlock) void k_rmsnorm_bwd(const T* __restrict__ dy
     float v = 0.f;
 #pragma unroll
     for (int w = 0; w < kWavesPerBlock; ++w) v += s_dg[(size_t)w * d + c];
-    unsafeAtomicAdd(dg + c, v);
+    if (part_out) part_out[(size_t)blockIdx.x * d + c] = v;
+    else unsafeAtomicAdd(dg + c, v);
   }
+}
+
+// dg[c] += sum over n rows of part[row][c].  A block takes 64 columns and one of gridDim.y runs of rows: its four
+// wavefronts stride the run's rows, fold in LDS, and add one value per column atomically (gridDim.y adds per
+// address in all).
+__global__ __launch_bounds__(kBlock) void k_colsum_add(const float* __restrict__ part, int n, int d, float* __restrict__ dg) {
+  __shared__ float s_part[kWavesPerBlock][64];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, c = blockIdx.x * 64 + lane;
+  const int per = (n + gridDim.y - 1) / gridDim.y, r0 = blockIdx.y * per, r1 = min(n, r0 + per);
+  float v0 = 0.f, v1 = 0.f;
+  if (c < d) {
+    int r = r0 + w;
+    for (; r + kWavesPerBlock < r1; r += 2 * kWavesPerBlock) {
+      v0 += part[(size_t)r * d + c];
+      v1 += part[(size_t)(r + kWavesPerBlock) * d + c];
+    }
+    if (r < r1) v0 += part[(size_t)r * d + c];
+  }
+  s_part[w][lane] = v0 + v1;
+  __syncthreads();
+  if (w == 0 && c < d) unsafeAtomicAdd(dg + c, (s_part[0][lane] + s_part[1][lane]) + (s_part[2][lane] + s_part[3][lane]));
 }
 
 template <class T>
@@ -495,7 +520,7 @@ void rmsnorm_fwd(hipStream_t s, int dtype, const void* x, const void* g, int64_t
 
 template <class T>
 static void rmsnorm_bwd_t(hipStream_t s, const T* dy, const T* x, const T* g, const float* rstd, const T* dres,
-                          int64_t R, int d, T* dx, float* dg) {
+                          int64_t R, int d, T* dx, float* dg, float* part, int64_t part_floats) {
   if (R <= 0) return;
   // the gain-gradient fold keeps one row of d floats per wavefront in LDS: 64 KB at d = 4096
   bool vec = d % 8 == 0 && d <= 4096 && aligned16<T>(x) && aligned16<T>(g) && aligned16<T>(dy) && aligned16<T>(dx) &&
@@ -508,17 +533,19 @@ static void rmsnorm_bwd_t(hipStream_t s, const T* dy, const T* x, const T* g, co
   int grid = grid_for_rows(R, kWavesPerBlock * 4, 1024);  // >= 4 rows per wavefront amortise the dg fold
   size_t lds = (size_t)d * sizeof(float) * kWavesPerBlock;
   int nv = (d + 511) / 512;
-#define SP_CASE(N) hipLaunchKernelGGL((k_rmsnorm_bwd<T, N>), dim3(grid), dim3(kBlock), lds, s, dy, x, g, rstd, dres, R, d, dx, dg)
+  float* pp = (part && (int64_t)grid * d <= part_floats && grid > 8) ? part : nullptr;
+#define SP_CASE(N) hipLaunchKernelGGL((k_rmsnorm_bwd<T, N>), dim3(grid), dim3(kBlock), lds, s, dy, x, g, rstd, dres, R, d, dx, dg, pp)
   if (nv <= 1) SP_CASE(1); else if (nv <= 2) SP_CASE(2); else if (nv <= 4) SP_CASE(4); else if (nv <= 8) SP_CASE(8); else SP_CASE(16);
 #undef SP_CASE
+  if (pp) hipLaunchKernelGGL(k_colsum_add, dim3((d + 63) / 64, 8), dim3(kBlock), 0, s, pp, grid, d, dg);
 }
 
 void rmsnorm_bwd(hipStream_t s, int dtype, const void* dy, const void* x, const void* g, const float* rstd,
-                 const void* dres, int64_t R, int d, void* dx, float* dg) {
+                 const void* dres, int64_t R, int d, void* dx, float* dg, float* part, int64_t part_floats) {
   if (dtype == SP_BF16)
-    rmsnorm_bwd_t<bf16>(s, (const bf16*)dy, (const bf16*)x, (const bf16*)g, rstd, (const bf16*)dres, R, d, (bf16*)dx, dg);
+    rmsnorm_bwd_t<bf16>(s, (const bf16*)dy, (const bf16*)x, (const bf16*)g, rstd, (const bf16*)dres, R, d, (bf16*)dx, dg, part, part_floats);
   else
-    rmsnorm_bwd_t<float>(s, (const float*)dy, (const float*)x, (const float*)g, rstd, (const float*)dres, R, d, (float*)dx, dg);
+    rmsnorm_bwd_t<float>(s, (const float*)dy, (const float*)x, (const float*)g, rstd, (const float*)dres, R, d, (float*)dx, dg, part, part_floats);
 }
 
 void rope(hipStream_t s, int dtype, void* qk, int64_t R, int T, int nheads, int hd, int row_stride, float theta,
