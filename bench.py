@@ -20,10 +20,12 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 # HBM-side bytes per launch of the weight-gradient product at the default workload, from rocprofv3 --pmc
-# FETCH_SIZE (x 1.998, the factor a plain copy of known size gives) + WRITE_SIZE (x 1.000); see profiles/.
-# Valid for the kernel as it was when the counters were taken: set to None when k_gemm_mfma changes.
-GEMM_TN_C3_TRAFFIC_BYTES = 833.5e6
+# FETCH_SIZE (x 1.998, the factor a plain copy of known size gives) + WRITE_SIZE (x 1.000); see
+# profiles/c3_stage_counters_pmc.txt.  Valid for the kernel as it was when the counters were taken: set to None
+# when k_gemm_mfma changes.
+GEMM_TN_C3_TRAFFIC_BYTES = None
 
 
 def flops_per_token_layer(cfg):
@@ -221,10 +223,12 @@ def emulate_mode(args, w, torch, sp, synth):
     print(json.dumps(out))
 
 
-def cpu_baseline(key, synth):
-    """The CPU checker timed on a bounded sample of the same workload (float32 instantiation)."""
+def cpu_baseline(key, synth, full=False):
+    """The CPU checker timed on a bounded sample of the same workload (float32 instantiation); full: on the
+    whole workload instead (minutes to hours on the larger shapes)."""
     import numpy as np
     from oracle import skippipe_oracle as orc
+    whole_shape = full
     full = synth.CONFIGS[key]
     lib = orc.lib()
     try:
@@ -236,6 +240,8 @@ def cpu_baseline(key, synth):
         T = min(full["seq_len"], 128 if full["dim"] > 512 else full["seq_len"])
         cfg = synth.shrink(full, seq_len=T, seqs_per_mb=1, n_mb=min(2, full["n_mb"]),
                            vocab=min(full["vocab"], 4096))
+        if whole_shape:
+            cfg, T = dict(full), full["seq_len"] * full["seqs_per_mb"]
         paths, lens = synth.make_paths(cfg["n_stages"], cfg["n_mb"], *cfg["skip"], bool(cfg["swap"]), synth.BASE_SEED)
         named = synth.make_params(cfg, synth.BASE_SEED)
         tok, tgt = synth.make_tokens(cfg, synth.BASE_SEED)
@@ -245,6 +251,8 @@ def cpu_baseline(key, synth):
         toks = cfg["n_mb"] * T
         sample = (f"{cfg['n_mb']} microbatches x {T} tokens through the whole {full['n_stages']}-stage model "
                   f"(full widths, vocab {cfg['vocab']}), fwd+bwd+loss")
+        if whole_shape:
+            sample = "the whole workload"
     else:
         T = 2048 if full["dim"] <= 2048 else 512
         cfg = synth.shrink(full, seq_len=T, seqs_per_mb=1, n_mb=1, has_head=0, vocab=1024)
@@ -253,16 +261,26 @@ def cpu_baseline(key, synth):
         paths = np.full((1, cfg["n_stages"]), -1, np.int32)
         paths[0, :2] = (0, stage)
         lens = np.array([2], np.int32)
+        if whole_shape:    # every routed microbatch at full length through the stage (the head, if any, left out)
+            T = full["seq_len"]
+            all_paths, all_lens, stage = synth.stage_share_paths(key)
+            routed = [mb for mb in range(full["n_mb"]) if stage in all_paths[mb, :all_lens[mb]]]
+            cfg = synth.shrink(full, n_mb=len(routed), has_head=0, vocab=1024)
+            cfg["local_stage_begin"], cfg["local_stage_count"] = stage, 1
+            paths = np.full((len(routed), cfg["n_stages"]), -1, np.int32)
+            paths[:, 0] = 0; paths[:, 1] = stage
+            lens = np.full(len(routed), 2, np.int32)
         named = synth.make_params(cfg, synth.BASE_SEED)
         x = synth.make_activations(cfg, synth.BASE_SEED)
         dy = synth.make_upstream_grad(cfg, synth.BASE_SEED)
         t0 = time.perf_counter()
         orc.run_paths(cfg, named, paths, lens, x_in=x, dy_in=dy, dtype=np.float32)
         dt = time.perf_counter() - t0
-        toks = T
-        sample = (f"1 microbatch x {T} tokens through the {cfg['layers_per_stage']}-layer stage (full widths), "
-                  f"fwd+bwd, no head")
-    return dict(value=toks / dt, unit="tokens/s", cores=cores, kind="oracle", sample=sample, seconds=round(dt, 2))
+        toks = T * cfg["n_mb"]
+        sample = (f"{cfg['n_mb']} microbatch(es) x {T} tokens through the {cfg['layers_per_stage']}-layer stage (full "
+                  f"widths), fwd+bwd, no head")
+    return dict(value=toks / dt, unit="tokens/s (of the sample named in `sample`)", cores=cores, kind="oracle",
+                sample=sample, seconds=round(dt, 2))
 
 
 def main():
@@ -272,6 +290,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--oracle-full", action="store_true",
+                    help="time the CPU checker on the whole workload instead of the bounded sample (c1: seconds; c2 "
+                         "and c3: minutes; c4 and c5: hours)")
     ap.add_argument("--eval-skip", default=None, metavar="NUM/DEN",
                     help="whole-model workloads (c1, c2): time forward-only evaluation with this share of the "
                          "stages dropped per sample (a half stage where the count ends in .5) instead of training")
@@ -338,10 +359,17 @@ def main():
                              else None),
                     avg_launch_ms=round(p["ms"] / p["launches"], 4), launches_per_step=p["launches"] // args.steps,
                     share_of_step=round(p["ms"] / args.steps / (sec * 1e3), 3))
-    kernels = {k: dict(ms_per_step=round(v["ms"] / args.steps, 3),
-                       tflops=round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 1) if v["ms"] > 0 else None,
-                       launches_per_step=v["launches"] // args.steps)
-               for k, v in prof.items() if v["launches"]}
+    kernels = {}
+    for k, v in prof.items():
+        if not v["launches"]:
+            continue
+        e = dict(ms_per_step=round(v["ms"] / args.steps, 3), launches_per_step=v["launches"] // args.steps)
+        if k in sp.PROF_BYTES_CLASSES:     # bandwidth-bound: algorithmic bytes against the HBM peak
+            gbs = v["flops"] / (v["ms"] * 1e-3) / 1e9 if v["ms"] > 0 else 0.0
+            e.update(algorithmic_gbs=round(gbs, 1), frac_hbm_peak=round(gbs / PEAK_HBM_GBS, 4))
+        else:
+            e["tflops"] = round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 1) if v["ms"] > 0 else None
+        kernels[k] = e
 
     cfg = w["cfg"]
     tflops = w["flops"] / sec / 1e12
@@ -374,7 +402,7 @@ def main():
     }
     out["optimizer_step"] = optimizer_step(w, torch, sp)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(args.config, synth)
+        out["cpu_baseline"] = cpu_baseline(args.config, synth, full=args.oracle_full)
     w["ctx"].close()
     print(json.dumps(out))
 

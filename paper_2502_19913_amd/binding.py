@@ -353,7 +353,8 @@ def grad_reduce(replica_grads, out, scale: float = 1.0, stream=None):
 
 
 PROF_CLASSES = ["gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd", "attn_delta", "attn_dq", "attn_dkv", "gemm_plain",
-                "attn_plain"]
+                "attn_plain", "rmsnorm_fwd", "rmsnorm_bwd", "cross_entropy", "copy_rows", "swiglu"]
+PROF_BYTES_CLASSES = ("rmsnorm_fwd", "rmsnorm_bwd", "cross_entropy", "copy_rows", "swiglu")   # "flops" holds bytes
 
 
 def prof_begin():

@@ -117,7 +117,10 @@ void attention_flash_bwd(hipStream_t s, int B, int T, int H, int Hkv, int hd, co
 
 // ---- optional per-launch timing (see sp_prof_begin); classes:
 enum { PROF_GEMM_NT = 0, PROF_GEMM_NN = 1, PROF_GEMM_TN = 2, PROF_ATTN_FWD = 3, PROF_ATTN_DELTA = 4, PROF_ATTN_DQ = 5,
-       PROF_ATTN_DKV = 6, PROF_GEMM_PLAIN = 7, PROF_ATTN_PLAIN = 8, PROF_CLASSES = 9 };
+       PROF_ATTN_DKV = 6, PROF_GEMM_PLAIN = 7, PROF_ATTN_PLAIN = 8,
+       // bandwidth-bound kernels: the work recorded is algorithmic bytes, not flops
+       PROF_RMSNORM_FWD = 9, PROF_RMSNORM_BWD = 10, PROF_CROSS_ENTROPY = 11, PROF_COPY_ROWS = 12, PROF_SWIGLU = 13,
+       PROF_CLASSES = 14 };
 int prof_start(int cls, hipStream_t s);
 void prof_stop(int idx, hipStream_t s, double flops);
 

@@ -489,12 +489,16 @@ void embed_bwd(hipStream_t s, int dtype, const void* dx, const int32_t* tok, int
 
 void gather_slots(hipStream_t s, int dtype, const void* pool, const SlotList& sl, int64_t rows_per_slot, int d,
                   void* dst) {
+  const int pi = prof_start(PROF_COPY_ROWS, s);
   copy_rows(s, pool, dst, sl.n * rows_per_slot, d * elt_size(dtype), 1, nullptr, sl, rows_per_slot);
+  prof_stop(pi, s, 2.0 * sl.n * rows_per_slot * d * elt_size(dtype));
 }
 
 void scatter_slots(hipStream_t s, int dtype, const void* src, const SlotList& sl, int64_t rows_per_slot, int d,
                    void* pool) {
+  const int pi = prof_start(PROF_COPY_ROWS, s);
   copy_rows(s, src, pool, sl.n * rows_per_slot, d * elt_size(dtype), 2, nullptr, sl, rows_per_slot);
+  prof_stop(pi, s, 2.0 * sl.n * rows_per_slot * d * elt_size(dtype));
 }
 
 template <class T>
@@ -514,8 +518,10 @@ static void rmsnorm_fwd_t(hipStream_t s, const T* x, const T* g, int64_t R, int 
 
 void rmsnorm_fwd(hipStream_t s, int dtype, const void* x, const void* g, int64_t R, int d, float eps, void* y,
                  float* rstd) {
+  const int pi = prof_start(PROF_RMSNORM_FWD, s);
   if (dtype == SP_BF16) rmsnorm_fwd_t<bf16>(s, (const bf16*)x, (const bf16*)g, R, d, eps, (bf16*)y, rstd);
   else rmsnorm_fwd_t<float>(s, (const float*)x, (const float*)g, R, d, eps, (float*)y, rstd);
+  prof_stop(pi, s, 2.0 * R * d * elt_size(dtype));   // x read, y written
 }
 
 template <class T>
@@ -542,10 +548,12 @@ static void rmsnorm_bwd_t(hipStream_t s, const T* dy, const T* x, const T* g, co
 
 void rmsnorm_bwd(hipStream_t s, int dtype, const void* dy, const void* x, const void* g, const float* rstd,
                  const void* dres, int64_t R, int d, void* dx, float* dg, float* part, int64_t part_floats) {
+  const int pi = prof_start(PROF_RMSNORM_BWD, s);
   if (dtype == SP_BF16)
     rmsnorm_bwd_t<bf16>(s, (const bf16*)dy, (const bf16*)x, (const bf16*)g, rstd, (const bf16*)dres, R, d, (bf16*)dx, dg, part, part_floats);
   else
     rmsnorm_bwd_t<float>(s, (const float*)dy, (const float*)x, (const float*)g, rstd, (const float*)dres, R, d, (float*)dx, dg, part, part_floats);
+  prof_stop(pi, s, (dres ? 4.0 : 3.0) * R * d * elt_size(dtype));   // dy, x (, dres) read, dx written
 }
 
 void rope(hipStream_t s, int dtype, void* qk, int64_t R, int T, int nheads, int hd, int row_stride, float theta,
@@ -582,11 +590,15 @@ static void swiglu_t(hipStream_t s, bool bwd, const T* da, const T* gu, int64_t 
 }
 
 void swiglu_fwd(hipStream_t s, int dtype, const void* gu, int64_t R, int h, void* a) {
+  const int pi = prof_start(PROF_SWIGLU, s);
+  struct Stop { int pi; hipStream_t s; double b; ~Stop() { prof_stop(pi, s, b); } } stop{pi, s, 3.0 * R * h * elt_size(dtype)};
   if (dtype == SP_BF16) swiglu_t<bf16>(s, false, nullptr, (const bf16*)gu, R, h, (bf16*)a);
   else swiglu_t<float>(s, false, nullptr, (const float*)gu, R, h, (float*)a);
 }
 
 void swiglu_bwd(hipStream_t s, int dtype, const void* da, const void* gu, int64_t R, int h, void* dgu) {
+  const int pi = prof_start(PROF_SWIGLU, s);
+  struct Stop { int pi; hipStream_t s; double b; ~Stop() { prof_stop(pi, s, b); } } stop{pi, s, 5.0 * R * h * elt_size(dtype)};
   if (dtype == SP_BF16) swiglu_t<bf16>(s, true, (const bf16*)da, (const bf16*)gu, R, h, (bf16*)dgu);
   else swiglu_t<float>(s, true, (const float*)da, (const float*)gu, R, h, (float*)dgu);
 }
@@ -599,6 +611,8 @@ void count_targets(hipStream_t s, const int32_t* tgt, int n_mb, int64_t rows_per
 void cross_entropy(hipStream_t s, int dtype, void* logits, const int32_t* tgt, int64_t row0, int64_t R, int V,
                    int64_t rows_per_mb, const int32_t* counts, float inv_n_mb, float* loss_mb) {
   if (R <= 0) return;
+  const int pi = prof_start(PROF_CROSS_ENTROPY, s);
+  struct Stop { int pi; hipStream_t s; double b; ~Stop() { prof_stop(pi, s, b); } } stop{pi, s, 2.0 * R * V * elt_size(dtype)};   // logits read, dlogits written
   bool vec = V % 8 == 0 && ((uintptr_t)logits % 16) == 0;
 #define SP_CE(T, VEC)                                                                                          \
   hipLaunchKernelGGL((k_cross_entropy<T, VEC>), dim3((unsigned)R), dim3(kBlock), 0, s, (T*)logits, tgt, row0, V, \
