@@ -77,30 +77,50 @@ __device__ __forceinline__ void store4(bf16* q, const float4& x) {
   *reinterpret_cast<uint2*>(q) = make_uint2(pack_bf16(x.x, x.y), pack_bf16(x.z, x.w));
 }
 
+__device__ __forceinline__ float4 load4_stream(const float* q) {
+  typedef __attribute__((ext_vector_type(4))) float f4;
+  const f4 v = __builtin_nontemporal_load(reinterpret_cast<const f4*>(q));
+  return make_float4(v[0], v[1], v[2], v[3]);
+}
+__device__ __forceinline__ void store4_stream(float* q, const float4& x) {
+  typedef __attribute__((ext_vector_type(4))) float f4;
+  const f4 v = {x.x, x.y, x.z, x.w};
+  __builtin_nontemporal_store(v, reinterpret_cast<f4*>(q));
+}
+
+// Every element is read once and written once: all accesses carry the streaming hint, and a thread keeps two
+// quads (8 loads) in flight.
 template <class LP>   // LP: float (a plain copy) or bf16
 __global__ __launch_bounds__(kBlock) void k_adamw(float* __restrict__ p, const float* __restrict__ g, float* __restrict__ m,
                                                   float* __restrict__ v, LP* __restrict__ lp, int64_t n, Hyper h,
                                                   const Scalars* __restrict__ sc) {
   const float coef = sc->coef;
-  const int64_t n4 = n / 4;
-  for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n4; i += (int64_t)gridDim.x * kBlock) {
-    float4 pp = reinterpret_cast<float4*>(p)[i], mm = reinterpret_cast<float4*>(m)[i], vv = reinterpret_cast<float4*>(v)[i];
-    const float4 gg = reinterpret_cast<const float4*>(g)[i];
+  const int64_t n4 = n / 4, stride = (int64_t)gridDim.x * kBlock;
+  auto one = [&](int64_t i, float4 pp, float4 gg, float4 mm, float4 vv) {
     pp.x = update_one(pp.x, gg.x * coef, mm.x, vv.x, h);
     pp.y = update_one(pp.y, gg.y * coef, mm.y, vv.y, h);
     pp.z = update_one(pp.z, gg.z * coef, mm.z, vv.z, h);
     pp.w = update_one(pp.w, gg.w * coef, mm.w, vv.w, h);
-    reinterpret_cast<float4*>(p)[i] = pp;
-    reinterpret_cast<float4*>(m)[i] = mm;
-    reinterpret_cast<float4*>(v)[i] = vv;
+    store4_stream(p + 4 * i, pp);
+    store4_stream(m + 4 * i, mm);
+    store4_stream(v + 4 * i, vv);
     if (lp) store4(lp + 4 * i, pp);   // one 8-byte (bf16) or 16-byte (float) store
+  };
+  int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  for (; i + stride < n4; i += 2 * stride) {
+    const int64_t j = i + stride;
+    const float4 p0 = load4_stream(p + 4 * i), g0 = load4_stream(g + 4 * i), m0 = load4_stream(m + 4 * i), v0 = load4_stream(v + 4 * i);
+    const float4 p1 = load4_stream(p + 4 * j), g1 = load4_stream(g + 4 * j), m1 = load4_stream(m + 4 * j), v1 = load4_stream(v + 4 * j);
+    one(i, p0, g0, m0, v0);
+    one(j, p1, g1, m1, v1);
   }
+  if (i < n4) one(i, load4_stream(p + 4 * i), load4_stream(g + 4 * i), load4_stream(m + 4 * i), load4_stream(v + 4 * i));
   if (blockIdx.x == 0)
-    for (int64_t i = n4 * 4 + threadIdx.x; i < n; i += kBlock) {
-      float mm = m[i], vv = v[i];
-      const float pn = update_one(p[i], g[i] * coef, mm, vv, h);
-      p[i] = pn; m[i] = mm; v[i] = vv;
-      if (lp) lp[i] = from_float<LP>(pn);
+    for (int64_t t = n4 * 4 + threadIdx.x; t < n; t += kBlock) {
+      float mm = m[t], vv = v[t];
+      const float pn = update_one(p[t], g[t] * coef, mm, vv, h);
+      p[t] = pn; m[t] = mm; v[t] = vv;
+      if (lp) lp[t] = from_float<LP>(pn);
     }
 }
 
