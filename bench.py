@@ -25,7 +25,7 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 # FETCH_SIZE (x 1.998, the factor a plain copy of known size gives) + WRITE_SIZE (x 1.000); see
 # profiles/c3_stage_counters_pmc.txt.  Valid for the kernel as it was when the counters were taken: set to None
 # when k_gemm_mfma changes.
-GEMM_TN_C3_TRAFFIC_BYTES = None
+GEMM_TN_C3_TRAFFIC_BYTES = 816.2e6
 
 
 def flops_per_token_layer(cfg):
@@ -283,6 +283,35 @@ def cpu_baseline(key, synth, full=False):
                 sample=sample, seconds=round(dt, 2))
 
 
+def probe_mfma(torch, sp):
+    """Matrix cores alone (sp_probe_mfma_rate), 8 waves on each of the 256 CUs, about 10 ms per launch."""
+    g = torch.Generator(device="cuda").manual_seed(7)
+    srcs = {"zeros": torch.zeros(1 << 22, dtype=torch.bfloat16, device="cuda"),
+            "ones": torch.ones(1 << 22, dtype=torch.bfloat16, device="cuda"),
+            "normal": torch.randn(1 << 22, dtype=torch.float32, device="cuda", generator=g).to(torch.bfloat16)}
+    sink = torch.empty(256 * 512, dtype=torch.float32, device="cuda")
+    out = {}
+    for name, src in srcs.items():
+        iters = 10000
+        for _ in range(2):
+            sp.probe_mfma_rate(src, 256, iters, sink)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 10
+        a.record()
+        for _ in range(reps):
+            fl = sp.probe_mfma_rate(src, 256, iters, sink)
+        b.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b) / reps
+        tf = fl / (ms * 1e-3) / 1e12
+        # 1024 SIMDs x 1024 flops per cycle each at the rate of one 16x16x32 product per 16 cycles
+        out[name] = dict(ms_per_launch=round(ms, 3), tflops=round(tf, 1), frac_peak=round(tf / PEAK_BF16_TFLOPS, 4),
+                         implied_clock_ghz=round(tf * 1e12 / (1024 * 1024.0) / 1e9, 3))
+    print(json.dumps(dict(metric="mfma_only_rate", unit="TFLOP/s", peak=PEAK_BF16_TFLOPS, blocks=256,
+                          waves_per_block=8, operands=out)))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -304,6 +333,9 @@ def main():
                          "by the paper's node-distribution rule) and run them one stream per node")
     ap.add_argument("--one-group", action="store_true",
                     help="stage-share workloads: all routed microbatches as one group (upper bound of the rate)")
+    ap.add_argument("--probe-mfma", action="store_true",
+                    help="instead of a workload: the rate the matrix cores sustain on a registers-only loop of the "
+                         "product kernel's k-step, for zero, constant and random operands (one JSON line)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -315,6 +347,8 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
+    if args.probe_mfma:
+        return probe_mfma(torch, sp)
     w = build_workload(args.config, torch, sp, synth)
     if args.eval_skip:
         return eval_mode(args, w, torch, sp, synth)

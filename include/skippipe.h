@@ -342,6 +342,17 @@ int sp_grad_reduce(void* hip_stream, const float* const* replica_grads, int n_re
 int sp_prof_begin(void);
 int sp_prof_end(int n_classes, double* ms, double* flops, int64_t* launches);
 
+/* Measurement aid: what the matrix cores sustain with nothing else going on.  Launches n_blocks (1..65536)
+ * workgroups of 8 waves; every wave loads the 24 bf16 operand fragments of one 256 x 256 x 64 k-step of the
+ * product kernels from src (device, 16-byte aligned, src_bytes >= 16 bytes of bf16 values of the caller's
+ * choice, read modulo its size) and repeats that step's 64 v_mfma_f32_16x16x32_bf16 `iters` times with the
+ * fragments held in registers.  sink: device float [n_blocks * 512], overwritten.  *flops (host) receives
+ * the multiply-add flops of the launch; the caller times the launch on hip_stream.  Enqueued, not waited for.
+ * Used to separate the chip's clock / power ceiling for a given operand content from what a kernel loses to
+ * memory traffic and epilogues. */
+int sp_probe_mfma_rate(void* hip_stream, const void* src, int64_t src_bytes, int n_blocks, int iters, float* sink,
+                       double* flops);
+
 #ifdef __cplusplus
 }
 #endif

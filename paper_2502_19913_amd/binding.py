@@ -23,7 +23,7 @@ EXPORTS = ["sp_param_count", "sp_param_layout", "sp_workspace_bytes", "sp_make_p
            "sp_route_plan", "sp_schedule_paths", "sp_stage_sizes", "sp_strerror", "sp_create", "sp_destroy", "sp_reset", "sp_set_side_stream", "sp_embed_fwd", "sp_embed_bwd",
            "sp_stage_fwd", "sp_stage_bwd", "sp_head_fwd_bwd", "sp_run_paths", "sp_eval_paths", "sp_gemm", "sp_attention_fwd",
            "sp_attention_bwd", "sp_optim_workspace_bytes", "sp_optim_step", "sp_prof_begin", "sp_prof_end", "sp_input_status",
-           "sp_grad_reduce", "sp_optim_step_noalloc", "sp_ffn_up_fwd", "sp_ffn_down_bwd"]
+           "sp_grad_reduce", "sp_optim_step_noalloc", "sp_ffn_up_fwd", "sp_ffn_down_bwd", "sp_probe_mfma_rate"]
 
 
 class SpCfg(C.Structure):
@@ -350,6 +350,16 @@ def grad_reduce(replica_grads, out, scale: float = 1.0, stream=None):
     ptrs = (C.c_void_p * len(replica_grads))(*[g.data_ptr() for g in replica_grads])
     _check(lib().sp_grad_reduce(_stream_ptr(stream), ptrs, C.c_int(len(replica_grads)), C.c_int64(n), C.c_float(scale),
                                 _dptr(out)))
+
+
+def probe_mfma_rate(src, n_blocks, iters, sink, stream=None):
+    """sp_probe_mfma_rate: enqueue the registers-only matrix-core loop; returns the flops of the launch."""
+    import torch
+    assert src.is_cuda and sink.is_cuda and sink.dtype == torch.float32 and sink.numel() >= n_blocks * 512
+    fl = C.c_double(0.0)
+    _check(lib().sp_probe_mfma_rate(_stream_ptr(stream), _dptr(src), C.c_int64(src.numel() * src.element_size()),
+                                    C.c_int(n_blocks), C.c_int(iters), _dptr(sink), C.byref(fl)))
+    return fl.value
 
 
 PROF_CLASSES = ["gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd", "attn_delta", "attn_dq", "attn_dkv", "gemm_plain",

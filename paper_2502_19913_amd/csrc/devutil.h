@@ -83,12 +83,18 @@ __device__ __forceinline__ u32x4 make_desc(const void* p, uint32_t bytes) {   //
   u32x4 d = {(uint32_t)a, (uint32_t)(a >> 32) & 0xffffu, bytes, 0x00020000u};
   return d;
 }
+// The statements overwrite m0 and say so in their clobber lists, so that the compiler re-creates any m0 value of
+// its own after them.  m0 is a register the compiler never allocates, and clang warns about such a register on a
+// clobber list whatever the reason: the warning is switched off for these two statements only.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void load_to_lds16(u32x4 desc, lds_ptr lds, uint32_t voff) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds), "v"(voff), "s"(desc) : "memory");
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(lds), "v"(voff), "s"(desc) : "memory", "m0");
 }
 __device__ __forceinline__ void load_to_lds4(u32x4 desc, lds_ptr lds, uint32_t voff) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds" ::"s"(lds), "v"(voff), "s"(desc) : "memory");
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, 0 offen lds" ::"s"(lds), "v"(voff), "s"(desc) : "memory", "m0");
 }
+#pragma clang diagnostic pop
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll

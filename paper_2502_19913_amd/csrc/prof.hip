@@ -16,6 +16,51 @@ std::vector<Rec> g_recs;
 std::vector<hipEvent_t> g_pool;
 std::mutex g_mu;
 
+// Matrix cores alone: every wave keeps the 24 operand fragments of one 256 x 256 x 64 k-step of the product
+// kernel in registers and repeats that step's 64 v_mfma_f32_16x16x32_bf16 `iters` times: no LDS, no global
+// loads inside the loop.  The rate it sustains is what the chip's clock and power management leave of the
+// published peak for a given operand content (zeros toggle nothing; random values draw full power).
+typedef __attribute__((ext_vector_type(8))) __bf16 probe_bf16x8;
+typedef __attribute__((ext_vector_type(4))) float probe_f32x4;
+
+__global__ __launch_bounds__(512, 1) void k_mfma_probe(const uint4* __restrict__ src, int64_t n_quads, int iters,
+                                                      float* __restrict__ sink) {
+  const int lane_id = threadIdx.x + blockIdx.x * 512;
+  probe_bf16x8 fa[2][8], fb[2][4];
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      uint4 q = src[((int64_t)lane_id * 24 + k * 12 + j) % n_quads];
+      fa[k][j] = *reinterpret_cast<probe_bf16x8*>(&q);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      uint4 q = src[((int64_t)lane_id * 24 + k * 12 + 8 + i) % n_quads];
+      fb[k][i] = *reinterpret_cast<probe_bf16x8*>(&q);
+    }
+  }
+  probe_f32x4 acc[8][4];
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[j][i] = probe_f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int k = 0; k < 2; ++k)
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[j][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[k][j], fb[k][i], acc[j][i], 0, 0, 0);
+  }
+  probe_f32x4 t = probe_f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) t += acc[j][i];
+  sink[lane_id] = t[0] + t[1] + t[2] + t[3];
+}
+
 hipEvent_t take_event() {
   if (!g_pool.empty()) {
     hipEvent_t e = g_pool.back();
@@ -77,6 +122,19 @@ int sp_prof_end(int n_classes, double* ms, double* flops, int64_t* launches) {
   }
   g_recs.clear();
   return rc;
+}
+
+int sp_probe_mfma_rate(void* hip_stream, const void* src, int64_t src_bytes, int n_blocks, int iters, float* sink,
+                       double* flops) {
+  if (!src || !sink || !flops || src_bytes < 16 || n_blocks < 1 || n_blocks > 65536 || iters < 1)
+    return fail(SP_EINVAL, "probe_mfma_rate: bad argument");
+  if (reinterpret_cast<uintptr_t>(src) % 16) return fail(SP_EINVAL, "probe_mfma_rate: src not 16-byte aligned");
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  k_mfma_probe<<<dim3(n_blocks), dim3(512), 0, s>>>(static_cast<const uint4*>(src), src_bytes / 16, iters, sink);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail((int)e, "probe_mfma_rate launch");
+  *flops = (double)n_blocks * 8 * (double)iters * 64 * (2.0 * 16 * 16 * 32);
+  return SP_OK;
 }
 
 }  // extern "C"
