@@ -328,6 +328,9 @@ def main():
     ap.add_argument("--serial", action="store_true",
                     help="keep the weight-gradient products in line on the one stream (no side stream) for the "
                          "whole run; by default only the per-launch timing pass runs that way")
+    ap.add_argument("--side-always", action="store_true",
+                    help="weight-gradient products on the side stream for every group (by default only for groups "
+                         "whose products are short enough to gain from it)")
     ap.add_argument("--emulate-nodes", action="store_true",
                     help="whole-model workloads (c1, c2): schedule the microbatches over emulated nodes (stage sizes "
                          "by the paper's node-distribution rule) and run them one stream per node")
@@ -357,7 +360,7 @@ def main():
     if args.one_group and not w["whole"]:
         mbs = sorted(m for _, _, g in w["plan"] for m in g)
         w["plan"] = [(w["plan"][0][0], w["stage"], mbs)]
-    w["ctx"].set_side_stream(not args.serial)
+    w["ctx"].set_side_stream(0 if args.serial else 2 if args.side_always else 1)
     for _ in range(args.warmup):
         step(w)
     torch.cuda.synchronize()

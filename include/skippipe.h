@@ -193,8 +193,12 @@ int sp_destroy(sp_ctx* ctx);
 /* sp_stage_bwd (and sp_run_paths through it) runs the four weight-gradient products of a layer on a second
  * stream owned by the context, beside the chain that carries the activation gradient down the layers, and
  * joins that stream back into the caller's before it returns: for the caller all work is still ordered on
- * its own stream.  enabled = 0 keeps everything in line on the caller's stream (the per-launch timings of
- * sp_prof_begin/end are then not inflated by kernels that share the GPU); the default is 1. */
+ * its own stream.  enabled = 1 (the default) does so for the groups it pays for: those whose R x d products
+ * have fewer than 640 tiles of 256 x 256 (about 2.5 rounds of the 256 CUs), where the second stream fills
+ * partly idle rounds; larger groups run in line, where two long products at once only disturb each other.
+ * enabled = 2 uses the second stream for every group; enabled = 0 keeps everything in line on the caller's
+ * stream (the per-launch timings of sp_prof_begin/end are then not inflated by kernels that share the GPU).
+ * SP_EINVAL for other values.  Results differ between the settings only in the order of float additions. */
 int sp_set_side_stream(sp_ctx* ctx, int enabled);
 
 /* Forgets every saved forward (e.g. after an aborted iteration). */

@@ -253,8 +253,9 @@ class Context:
         """Waits for the stream; raises SpError(SP_EINVAL) if a kernel met a token id or target out of range."""
         _check(lib().sp_input_status(self._h))
 
-    def set_side_stream(self, enabled: bool):
-        _check(lib().sp_set_side_stream(self._h, C.c_int(1 if enabled else 0)))
+    def set_side_stream(self, enabled):
+        """0 / False: weight gradients in line; 1 / True: on the second stream where that pays (default); 2: always."""
+        _check(lib().sp_set_side_stream(self._h, C.c_int(int(enabled))))
 
     def eval_paths(self, params, tokens, targets, paths: np.ndarray, lens: np.ndarray, half=None):
         paths = np.ascontiguousarray(paths, np.int32)

@@ -37,6 +37,21 @@ __device__ __forceinline__ void load8(const bf16* p, float (&v)[8]) {
   v[4] = bf16_bits_to_float(u.z & 0xffffu); v[5] = bf16_bits_to_float(u.z >> 16);
   v[6] = bf16_bits_to_float(u.w & 0xffffu); v[7] = bf16_bits_to_float(u.w >> 16);
 }
+// 8 bf16 values held as 16 bytes -> 8 floats
+__device__ __forceinline__ void unpack8(const uint4& v, float (&x)[8]) {
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int e = 0; e < 4; ++e) { x[2 * e] = bf16_bits_to_float(w[e] & 0xffffu); x[2 * e + 1] = bf16_bits_to_float(w[e] >> 16); }
+}
+// Tells the compiler that the four registers may have changed: values derived from them before this point are
+// not kept alive for reuse after it (a kernel that holds many packed values and unpacks them in two passes would
+// otherwise keep the unpacked floats of the first pass, at twice the registers).
+__device__ __forceinline__ void forget_derived(uint4& v) { asm volatile("" : "+v"(v.x), "+v"(v.y), "+v"(v.z), "+v"(v.w)); }
+// The same, and nothing derived from v after this point is computed before `after` has its value: keeps the
+// pieces of an unrolled loop in sequence where the scheduler would otherwise unpack all of them at once.
+__device__ __forceinline__ void forget_derived(uint4& v, float& after) {
+  asm volatile("" : "+v"(v.x), "+v"(v.y), "+v"(v.z), "+v"(v.w), "+v"(after));
+}
 __device__ __forceinline__ void store8(float* p, const float (&v)[8]) {
   *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
   *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
@@ -53,6 +68,11 @@ __device__ __forceinline__ void store16_stream(void* p, const uint4& u) {
   typedef __attribute__((ext_vector_type(4))) unsigned int u4;
   const u4 w = {u.x, u.y, u.z, u.w};
   __builtin_nontemporal_store(w, reinterpret_cast<u4*>(p));
+}
+__device__ __forceinline__ uint4 load16_stream(const void* p) {
+  typedef __attribute__((ext_vector_type(4))) unsigned int u4;
+  const u4 w = __builtin_nontemporal_load(reinterpret_cast<const u4*>(p));
+  return make_uint4(w[0], w[1], w[2], w[3]);
 }
 __device__ __forceinline__ void store8_stream(bf16* p, const float (&v)[8]) {
   uint4 u;

@@ -136,7 +136,7 @@ struct sp_ctx {
   hipStream_t side;
   hipEvent_t ready[4], done[2][4], joined;
   bool done_set[2][4];
-  bool use_side;     // false: weight gradients run in line on the caller's stream
+  int use_side;      // 0: weight gradients run in line on the caller's stream; 1: beside it when that pays; 2: always
   Carve w;
   size_t arena_top;
   std::vector<Record> records;
@@ -215,7 +215,7 @@ int sp_create(const sp_cfg* cfg, void* hip_stream, int n_mb_max, int n_visits_ma
     return fail(SP_ENOMEM, std::string("hipMalloc of the workspace failed: ") + hipGetErrorString(e));
   }
   c->side = nullptr;
-  c->use_side = true;
+  c->use_side = 1;
   e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
   for (int i = 0; i < 4 && e == hipSuccess; ++i) {
     e = hipEventCreateWithFlags(&c->ready[i], hipEventDisableTiming);
@@ -260,7 +260,8 @@ int sp_destroy(sp_ctx* ctx) {
 
 int sp_set_side_stream(sp_ctx* ctx, int enabled) {
   if (!ctx) return fail(SP_EINVAL, "ctx is null");
-  ctx->use_side = enabled != 0;
+  if (enabled < 0 || enabled > 2) return fail(SP_EINVAL, "set_side_stream: enabled must be 0, 1 or 2");
+  ctx->use_side = enabled;
   return SP_OK;
 }
 
@@ -406,7 +407,13 @@ int sp_stage_bwd(sp_ctx* ctx, int stage, const void* params, void* dact_pool, co
   float* delta = (float*)at(ctx, ctx->w.t_delta);
   float* dgpart = (float*)at(ctx, ctx->w.dgpart);
   const int64_t dgpart_n = (int64_t)kRmsPartRows * D.d;
-  hipStream_t side = ctx->use_side ? ctx->side : s;
+  // A second stream pays while the layer's products are short: their partly filled last rounds of tiles take in
+  // work of the other stream.  Products of many rounds only get in each other's way (workgroups of two kernels
+  // interleave on the CUs and the tiles an XCD holds no longer share panels): measured 3 - 7 % slower from about
+  // 2.5 rounds of 256 x 256 tiles of the R x d products on.
+  constexpr int64_t kSideMaxTiles = 640;
+  const bool side_pays = ((R + 255) / 256) * ((D.d + 255) / 256) < kSideMaxTiles;
+  hipStream_t side = ctx->use_side == 2 || (ctx->use_side == 1 && side_pays) ? ctx->side : s;
   for (int p = 0; p < 2; ++p)
     for (int i = 0; i < 4; ++i) ctx->done_set[p][i] = false;
   // weight gradient k of the layer (0: down, 1: gate/up, 2: output, 3: qkv) on the side stream, once its input

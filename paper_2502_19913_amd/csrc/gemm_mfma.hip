@@ -5,8 +5,11 @@
 // One workgroup of 8 wavefronts owns a 256x256 tile of the output (128x128 when the product has too few
 // 256-tiles to occupy the CUs) and walks the reduction dimension in steps of 64.  Operand tiles go from
 // memory straight into LDS (buffer loads with the LDS modifier: no staging registers, no LDS stores; the
-// hardware range check returns zero past the end of an operand, so ragged edges need no branches), one
-// step ahead of the MFMAs, into two stages (64 KB each for the large tile); one barrier per step.
+// hardware range check returns zero past the end of an operand, so ragged edges need no branches).  The
+// small tile keeps two stages of A and B, loaded one step ahead, with one barrier per step (two workgroups per
+// CU overlap each other).  The large tile fills the CU's 160 KB of LDS alone (two tiles of A, three of B) and
+// runs the alternating-phase loop described where it stands: the two wavefronts of a SIMD take turns between
+// reading fragments and issuing MFMAs, half a step apart.
 //
 // LDS layouts.  A load instruction fills 1 KiB of LDS in lane order, so tiles are unpadded and the
 // 16-byte chunks of a row are permuted by an XOR with bits of the row number (see Operand), which
@@ -232,12 +235,6 @@ __device__ __forceinline__ bf16x8 read_frag32(const char* tile, int row_base, in
 //   kEpiSwigluBwd  op 1, N = h: the product is d(act); with gate|up read from R[M, 2h], C[M, 2h] receives
 //                  d(gate) | d(up); d(act) itself is not stored
 enum { kEpiPlain = 0, kEpiRope = 1, kEpiSwiglu = 2, kEpiSwigluBwd = 3 };
-
-__device__ __forceinline__ void unpack8(const uint4& v, float (&x)[8]) {
-  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-  for (int e = 0; e < 4; ++e) { x[2 * e] = bf16_bits_to_float(w[e] & 0xffffu); x[2 * e + 1] = bf16_bits_to_float(w[e] >> 16); }
-}
 
 template <int OP, bool KMASK, int EPI, int TILE, bool PP = false>
 __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__ A, const bf16* __restrict__ B,

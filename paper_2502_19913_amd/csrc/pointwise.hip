@@ -1,6 +1,9 @@
 // Bandwidth-bound kernels of the stage: embedding, slot gather/scatter, RMSNorm, rotary embedding,
 // SwiGLU and cross-entropy, each forward and backward.  One wavefront (64 lanes) owns one row
 // wherever a row reduction is needed; rows are read with 16-byte loads when the width allows.
+#include <algorithm>
+#include <type_traits>
+
 #include "devutil.h"
 #include "internal.h"
 
@@ -216,6 +219,107 @@ __global__ __launch_bounds__(kBlock) void k_rmsnorm_bwd(const T* __restrict__ dy
     for (int w = 0; w < kWavesPerBlock; ++w) v += s_dg[(size_t)w * d + c];
     if (part_out) part_out[(size_t)blockIdx.x * d + c] = v;
     else unsafeAtomicAdd(dg + c, v);
+  }
+}
+
+// The same for bf16, columns instead of rows divided among the wavefronts: the block's four wavefronts share
+// each row (wavefront w takes the 512-column pieces w, w + 4, ..), so a lane's gain and its gain-gradient sums
+// are NVW x 8 values for the whole kernel and nothing has to be folded across wavefronts at the end.  RPI rows are
+// in flight together (dy, x and the added gradient all loaded before the first is used); the four partial sums
+// of a row's mean meet in LDS, one barrier per RPI rows (two sets of slots, alternating, so that the next
+// round's sums never overwrite one still being read).
+template <int NVW, int RPI, bool HAS_RES>
+__global__ __launch_bounds__(kBlock) void k_rmsnorm_bwd_cols(const bf16* __restrict__ dy, const bf16* __restrict__ x,
+                                                             const bf16* __restrict__ g, const float* __restrict__ rstd,
+                                                             const bf16* __restrict__ dres, int64_t R, int d,
+                                                             bf16* __restrict__ dx, float* __restrict__ dg,
+                                                             float* __restrict__ part_out) {
+  __shared__ float s_m[2][RPI][kWavesPerBlock];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int col[NVW];
+  uint32_t coff[NVW];   // byte offset of the piece in a row; 0 for a lane past the end of the row (loads stay in bounds, the
+                        // lane's gain is zero and nothing of it is stored)
+  float gv[NVW][8], acc[NVW][8];
+#pragma unroll
+  for (int i = 0; i < NVW; ++i) {
+    col[i] = ((i * kWavesPerBlock + wave) * 64 + lane) * 8;
+    coff[i] = col[i] < d ? (uint32_t)col[i] * 2u : 0u;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { acc[i][j] = 0.f; gv[i][j] = 0.f; }
+    if (col[i] < d) load8(g + col[i], gv[i]);
+  }
+  const float inv_d = 1.0f / (float)d;
+  // a row's (uniform) byte offset + the lane's 32-bit byte offset: one address register per piece for all streams
+  const char* const dyb = reinterpret_cast<const char*>(dy);
+  const char* const xb = reinterpret_cast<const char*>(x);
+  const char* const resb = reinterpret_cast<const char*>(dres);
+  char* const dxb = reinterpret_cast<char*>(dx);
+  int par = 0;
+#pragma nounroll
+  for (int64_t r0 = (int64_t)blockIdx.x * RPI; r0 < R; r0 += (int64_t)gridDim.x * RPI, par ^= 1) {
+    // all loads of the round first, unconditionally: a row past the end reads the last row again and counts
+    // for nothing (its rstd is taken as zero)
+    uint4 qdy[RPI][NVW], qx[RPI][NVW], qres[HAS_RES ? RPI : 1][NVW];
+#pragma unroll
+    for (int rr = 0; rr < RPI; ++rr) {
+      const size_t rb = (size_t)(r0 + rr < R ? r0 + rr : R - 1) * d * 2;
+#pragma unroll
+      for (int i = 0; i < NVW; ++i) {
+        qdy[rr][i] = *reinterpret_cast<const uint4*>(dyb + rb + coff[i]);
+        qx[rr][i] = *reinterpret_cast<const uint4*>(xb + rb + coff[i]);
+        if (HAS_RES) qres[rr][i] = *reinterpret_cast<const uint4*>(resb + rb + coff[i]);
+      }
+    }
+    float dxh[RPI][NVW][8], xh[RPI][NVW][8], rs[RPI];
+#pragma unroll
+    for (int rr = 0; rr < RPI; ++rr) {
+      rs[rr] = r0 + rr < R ? rstd[r0 + rr] : 0.f;
+      float m = 0.f;
+#pragma unroll
+      for (int i = 0; i < NVW; ++i) {
+        unpack8(qdy[rr][i], dxh[rr][i]);
+        unpack8(qx[rr][i], xh[rr][i]);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          xh[rr][i][j] *= rs[rr];
+          acc[i][j] += dxh[rr][i][j] * xh[rr][i][j];   // dg partial
+          dxh[rr][i][j] *= gv[i][j];
+          m += dxh[rr][i][j] * xh[rr][i][j];
+        }
+      }
+      m = wave_sum(m);
+      if (lane == 0) s_m[par][rr][wave] = m;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int rr = 0; rr < RPI; ++rr) {
+      const bool row_in = r0 + rr < R;
+      const float m = ((s_m[par][rr][0] + s_m[par][rr][1]) + (s_m[par][rr][2] + s_m[par][rr][3])) * inv_d;
+      const size_t rb = (size_t)(row_in ? r0 + rr : R - 1) * d * 2;
+#pragma unroll
+      for (int i = 0; i < NVW; ++i) {
+        float o[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) o[j] = rs[rr] * (dxh[rr][i][j] - xh[rr][i][j] * m);
+        if (HAS_RES) {
+          float rv[8];
+          unpack8(qres[rr][i], rv);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) o[j] += rv[j];
+        }
+        if (row_in && col[i] < d) store8(reinterpret_cast<bf16*>(dxb + rb + coff[i]), o);
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < NVW; ++i) {
+    if (col[i] < d) {
+      if (part_out) store8(part_out + (size_t)blockIdx.x * d + col[i], acc[i]);
+      else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) unsafeAtomicAdd(dg + col[i] + j, acc[i][j]);
+      }
+    }
   }
 }
 
@@ -460,6 +564,98 @@ __global__ __launch_bounds__(kBlock) void k_cross_entropy(T* __restrict__ logits
   }
 }
 
+// bf16 rows that fit a workgroup's registers (V <= NT * 8 * NCH): the row is read once, as NCH 16-byte pieces per
+// thread all in flight together, reduced from registers (block maximum, then the sum of exponentials), and
+// written once as (softmax - onehot) * scale: 4 V bytes of traffic per row instead of 6 V, and NCH loads per thread
+// outstanding instead of one.  Exponentials by the hardware's exp2 (the results are rounded to bf16).
+template <int NT, int NCH>
+__global__ __launch_bounds__(NT) void k_cross_entropy_row(bf16* __restrict__ logits, const int32_t* __restrict__ tgt,
+                                                          int64_t row0, int V, int64_t rows_per_mb,
+                                                          const int32_t* __restrict__ counts, float inv_n_mb,
+                                                          float* __restrict__ loss_mb) {
+  constexpr int NWV = NT / 64;
+  __shared__ float s_m[NWV], s_s[NWV], s_zt;
+  const int64_t r = blockIdx.x;
+  bf16* z = logits + r * (int64_t)V;
+  const int64_t grow = row0 + r;
+  const int t = tgt[grow];
+  const int mb = (int)(grow / rows_per_mb);
+  if (t < 0 || t >= V) {  // ignored position: no loss, zero gradient
+    for (int c = threadIdx.x * 8; c < V; c += NT * 8) store16_stream(z + c, make_uint4(0u, 0u, 0u, 0u));
+    return;
+  }
+  uint4 q[NCH];
+  char* const zb = reinterpret_cast<char*>(z);
+  const uint32_t toff = threadIdx.x * 16u;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int c = (i * NT + threadIdx.x) * 8;
+    // uniform piece base + 32-bit lane offset: one address register for all pieces
+    q[i] = c < V ? load16_stream(zb + (size_t)i * NT * 16 + toff) : make_uint4(0xff80ff80u, 0xff80ff80u, 0xff80ff80u, 0xff80ff80u);   // -inf
+  }
+  float mx = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    float v[8];
+    forget_derived(q[i], mx);
+    unpack8(q[i], v);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) mx = fmaxf(mx, v[j]);
+  }
+  mx = wave_max(mx);
+  if ((threadIdx.x & 63) == 0) s_m[threadIdx.x >> 6] = mx;
+  __syncthreads();
+  float bm = s_m[0];
+#pragma unroll
+  for (int w = 1; w < NWV; ++w) bm = fmaxf(bm, s_m[w]);
+  float sm = 0.f;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int c = (i * NT + threadIdx.x) * 8;
+    float v[8];
+    forget_derived(q[i], sm);
+    unpack8(q[i], v);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) sm += __expf(v[j] - bm);
+    const unsigned jt = (unsigned)(t - c);
+    if (jt < 8u) {   // this piece holds the target's logit: one thread of the block, once
+      float zt = v[0];
+#pragma unroll
+      for (int j = 1; j < 8; ++j) zt = jt == (unsigned)j ? v[j] : zt;
+      s_zt = zt;
+    }
+  }
+  sm = wave_sum(sm);
+  if ((threadIdx.x & 63) == 0) s_s[threadIdx.x >> 6] = sm;
+  __syncthreads();
+  float bs = 0.f;
+#pragma unroll
+  for (int w = 0; w < NWV; ++w) bs += s_s[w];
+  const float lse = bm + logf(bs);
+  const float cnt = (float)counts[mb];
+  const float scale = inv_n_mb / cnt;
+  if (threadIdx.x == 0) unsafeAtomicAdd(loss_mb + mb, (lse - s_zt) / cnt);
+  float last = 0.f;   // a value of the piece before: orders the pieces
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int c = (i * NT + threadIdx.x) * 8;
+    if (c < V) {
+      float v[8];
+      forget_derived(q[i], last);
+      unpack8(q[i], v);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] = __expf(v[j] - lse) * scale;
+      const unsigned jt = (unsigned)(t - c);
+      if (jt < 8u) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] -= jt == (unsigned)j ? scale : 0.f;
+      }
+      last = v[7];
+      store8_stream(reinterpret_cast<bf16*>(zb + (size_t)i * NT * 16 + toff), v);
+    }
+  }
+}
+
 template <class T> bool aligned16(const void* p) { return ((uintptr_t)p % 16) == 0; }
 
 }  // namespace
@@ -540,6 +736,23 @@ static void rmsnorm_bwd_t(hipStream_t s, const T* dy, const T* x, const T* g, co
   size_t lds = (size_t)d * sizeof(float) * kWavesPerBlock;
   int nv = (d + 511) / 512;
   float* pp = (part && (int64_t)grid * d <= part_floats && grid > 8) ? part : nullptr;
+  if constexpr (std::is_same<T, bf16>::value) {
+    // d <= 2048: one piece per lane, 4 rows in flight; d <= 4096: two pieces, 2 rows
+    const int rpi = d <= 2048 ? 4 : 2;
+    // three workgroups fit a CU (registers): one round of 256 x 3 resident workgroups that stride the rows
+    int gridc = (int)std::min<int64_t>((R + rpi - 1) / rpi, 768);
+    static_assert(768 <= kRmsPartRows, "one partial row per workgroup");
+    float* ppc = (part && (int64_t)gridc * d <= part_floats && gridc > 8) ? part : nullptr;
+#define SP_COLS(NVW, RPI)                                                                                              \
+  do {                                                                                                                 \
+    if (dres) hipLaunchKernelGGL((k_rmsnorm_bwd_cols<NVW, RPI, true>), dim3(gridc), dim3(kBlock), 0, s, dy, x, g, rstd, dres, R, d, dx, dg, ppc); \
+    else hipLaunchKernelGGL((k_rmsnorm_bwd_cols<NVW, RPI, false>), dim3(gridc), dim3(kBlock), 0, s, dy, x, g, rstd, dres, R, d, dx, dg, ppc);   \
+  } while (0)
+    if (d <= 2048) SP_COLS(1, 4); else SP_COLS(2, 2);
+#undef SP_COLS
+    if (ppc) hipLaunchKernelGGL(k_colsum_add, dim3((d + 63) / 64, 8), dim3(kBlock), 0, s, ppc, gridc, d, dg);
+    return;
+  }
 #define SP_CASE(N) hipLaunchKernelGGL((k_rmsnorm_bwd<T, N>), dim3(grid), dim3(kBlock), lds, s, dy, x, g, rstd, dres, R, d, dx, dg, pp)
   if (nv <= 1) SP_CASE(1); else if (nv <= 2) SP_CASE(2); else if (nv <= 4) SP_CASE(4); else if (nv <= 8) SP_CASE(8); else SP_CASE(16);
 #undef SP_CASE
@@ -614,6 +827,17 @@ void cross_entropy(hipStream_t s, int dtype, void* logits, const int32_t* tgt, i
   const int pi = prof_start(PROF_CROSS_ENTROPY, s);
   struct Stop { int pi; hipStream_t s; double b; ~Stop() { prof_stop(pi, s, b); } } stop{pi, s, 2.0 * R * V * elt_size(dtype)};   // logits read, dlogits written
   bool vec = V % 8 == 0 && ((uintptr_t)logits % 16) == 0;
+  if (dtype == SP_BF16 && vec && V <= 1024 * 8 * 16) {
+#define SP_CE_ROW(NT, NCH)                                                                                         \
+  hipLaunchKernelGGL((k_cross_entropy_row<NT, NCH>), dim3((unsigned)R), dim3(NT), 0, s, (bf16*)logits, tgt, row0, V, \
+                     rows_per_mb, counts, inv_n_mb, loss_mb)
+    if (V <= 256 * 8 * 4) SP_CE_ROW(256, 4);
+    else if (V <= 256 * 8 * 16) SP_CE_ROW(256, 16);
+    else if (V <= 512 * 8 * 16) SP_CE_ROW(512, 16);
+    else SP_CE_ROW(1024, 16);
+#undef SP_CE_ROW
+    return;
+  }
 #define SP_CE(T, VEC)                                                                                          \
   hipLaunchKernelGGL((k_cross_entropy<T, VEC>), dim3((unsigned)R), dim3(kBlock), 0, s, (T*)logits, tgt, row0, V, \
                      rows_per_mb, counts, inv_n_mb, loss_mb)

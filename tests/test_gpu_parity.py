@@ -160,6 +160,22 @@ def test_c1_full_shape_bf16():
     check_bf16(got, ref, "c1 bf16")
 
 
+@pytest.mark.parametrize("vocab", [8200, 40000, 70000, 131080])
+def test_head_and_loss_over_vocabulary_sizes_bf16(vocab):
+    # the loss kernel holds a row of logits in the registers of 256, 512 or 1024 threads, by the row's length;
+    # beyond 131072 entries it reads the row twice instead
+    cfg = dict(SMALL, vocab=vocab, dtype="bf16", n_stages=2, local_stage_count=2, layers_per_stage=1, n_mb=2)
+    named, tok, tgt = inputs(cfg, 21, bf16=True)
+    tgt = np.array(tgt)
+    tgt[0, 1, 5] = vocab - 1          # the last column, and the first, as targets
+    tgt[1, 0, 7] = 0
+    paths = np.array([[0, 1], [0, 1]], np.int32)
+    lens = np.array([2, 2], np.int32)
+    ref = orc.run_paths(cfg, named, paths, lens, tokens=tok, targets=tgt, dtype=np.float32)
+    got = run(cfg, named, paths, lens, tokens=tok, targets=tgt)
+    check_bf16(got, ref, f"vocab {vocab}")
+
+
 @pytest.mark.parametrize("name,shape", [
     ("c2", dict(seq_len=256, seqs_per_mb=2, n_mb=4, layers_per_stage=1, vocab=4096)),
 ])
@@ -260,6 +276,9 @@ def test_call_order_and_argument_errors():
         with pytest.raises(sp.SpError) as e:
             ctx.stage_fwd(1, params, act, [0, 0])
         assert e.value.code == -1
+        with pytest.raises(sp.SpError) as e:
+            ctx.set_side_stream(3)
+        assert e.value.code == -1
         with pytest.raises(sp.SpError):
             ctx.stage_fwd(7, params, act, [0])
         with pytest.raises(sp.SpError):
@@ -336,7 +355,7 @@ def test_side_stream_changes_nothing_but_the_order_of_float_additions():
     cfg["local_stage_begin"], cfg["local_stage_count"] = stage, 1
     named = {k: round_bf16(v) for k, v in synth.make_params(cfg, 12).items()}
     x = round_bf16(synth.make_activations(cfg, 12)); dy = round_bf16(synth.make_upstream_grad(cfg, 12))
-    a = run(cfg, named, paths, lens, x_in=x, dy_in=dy, side_stream=True)
+    a = run(cfg, named, paths, lens, x_in=x, dy_in=dy, side_stream=2)
     b = run(cfg, named, paths, lens, x_in=x, dy_in=dy, side_stream=False)
     np.testing.assert_array_equal(a["dx"], b["dx"])
     for k in a["grads"]:
