@@ -341,7 +341,7 @@ def main():
                          "product kernel's k-step, for zero, constant and random operands (one JSON line)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        print("bench.py measures one GPU: the library has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
         sys.exit(2)
     import torch
     from paper_2502_19913_amd import binding as sp

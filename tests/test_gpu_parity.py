@@ -1,6 +1,6 @@
 """GPU library against the CPU checker, element by element, on seeded synthetic inputs.
 
-Tolerances (stated target of this build): float mode 1e-4 relative on the loss and on every gradient
+Tolerances: float mode 1e-4 relative on the loss and on every gradient
 tensor (L2-relative per tensor); bfloat16 mode 1e-2 relative on the loss and per-tensor gradient cosine
 >= 0.999, with the checker fed the bf16-rounded parameters widened to float.  Beside the per-tensor norms every
 tensor also meets an element-wise bound, max|got - ref| <= tol * max|ref| (float: 1e-4; bfloat16: 5e-2, a few
