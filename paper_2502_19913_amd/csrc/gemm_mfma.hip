@@ -265,8 +265,12 @@ __global__ __launch_bounds__(kThreads) void k_gemm_mfma(const bf16* __restrict__
     id = x * per + min(x, rem) + id / 8;
   }
   const int ksteps = (K + BK - 1) / BK;
-  int64_t u = OP == 2 ? (int64_t)id * tiles * ksteps / gridDim.x : (int64_t)id * ksteps;
-  const int64_t u_end = OP == 2 ? (int64_t)(id + 1) * tiles * ksteps / gridDim.x : (int64_t)tiles * ksteps;
+  // OP 2: gridDim.x = tiles x s; id -> run id / tiles of tile id % tiles, so that the ids that share an XCD (a
+  // contiguous range) work on neighbouring tiles over the same k range and share their operand panels
+  const int s_runs = OP == 2 ? (int)gridDim.x / tiles : 1;
+  const int run = OP == 2 ? id / tiles : 0;
+  int64_t u = OP == 2 ? (int64_t)(id % tiles) * ksteps + (int64_t)run * ksteps / s_runs : (int64_t)id * ksteps;
+  const int64_t u_end = OP == 2 ? (int64_t)(id % tiles) * ksteps + (int64_t)(run + 1) * ksteps / s_runs : (int64_t)tiles * ksteps;
   while (u < u_end) {
   const int tile = (int)(u / ksteps), ks0 = (int)(u - (int64_t)tile * ksteps);
   const int ks1 = OP == 2 ? (int)min((int64_t)ksteps, ks0 + (u_end - u)) : ksteps;
