@@ -134,6 +134,20 @@ def test_gemm_rejects_bad_arguments():
         sp._check(sp.lib().sp_gemm(None, 0, 0, 8, 8, 8, None, sp._dptr(a), sp._dptr(a), None))
 
 
+def test_matrix_core_probe_counts_what_it_runs():
+    # all-ones operands: every accumulator entry grows by 32 per MFMA of 32 k, 2 per k-step repeat, and a lane's
+    # result is the sum of its 128 accumulator entries
+    iters, blocks = 3, 5
+    src = torch.ones(4096, dtype=torch.bfloat16, device="cuda")
+    sink = torch.zeros(blocks * 512, dtype=torch.float32, device="cuda")
+    flops = sp.probe_mfma_rate(src, blocks, iters, sink)
+    torch.cuda.synchronize()
+    assert flops == blocks * 8 * iters * 64 * 2.0 * 16 * 16 * 32
+    assert torch.all(sink == 128.0 * iters * 2 * 32).item()
+    with pytest.raises(sp.SpError):
+        sp._check(sp.lib().sp_probe_mfma_rate(None, sp._dptr(src), 8192, 0, 1, sp._dptr(sink), None))
+
+
 ATTN_CASES = [  # B, T, H, Hkv, hd
     (2, 64, 6, 6, 48), (1, 200, 4, 2, 64), (2, 333, 4, 1, 128), (1, 1, 2, 2, 64), (3, 17, 2, 1, 10),
     (1, 512, 2, 2, 128), (1, 640, 4, 4, 64),
