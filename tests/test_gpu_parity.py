@@ -160,6 +160,16 @@ def test_c1_full_shape_bf16():
     check_bf16(got, ref, "c1 bf16")
 
 
+def test_small_bf16_row_counts_that_fill_no_round():
+    # 25 tokens per microbatch: groups of 25, 50 and 75 rows, none a multiple of the rows a workgroup of the
+    # norm backward takes per round, nor of any tile height
+    cfg = dict(SMALL, dtype="bf16", seq_len=25, seqs_per_mb=1)
+    named, tok, tgt = inputs(cfg, 33, bf16=True)
+    ref = orc.run_paths(cfg, named, PATHS5, LENS5, tokens=tok, targets=tgt, dtype=np.float32)
+    got = run(cfg, named, PATHS5, LENS5, tokens=tok, targets=tgt)
+    check_bf16(got, ref, "ragged rows bf16")
+
+
 @pytest.mark.parametrize("vocab", [8200, 40000, 70000, 131080])
 def test_head_and_loss_over_vocabulary_sizes_bf16(vocab):
     # the loss kernel holds a row of logits in the registers of 256, 512 or 1024 threads, by the row's length;
