@@ -25,7 +25,6 @@ namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
-// u32x4 (devutil.h): one staged 16-byte chunk; a native vector, so staged tiles stay in registers
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -50,22 +49,14 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16& v, int u) {
   return o;
 }
 
-// LDS operand that pairs with pack8, gathered from a row-major [row][col] tile (row stride RS bytes)
-// with the LDS transpose read: MFMA row (lane % 32) = tile column col_base + lane % 32, and the 8
-// k-slots of lane half hh = tile rows row_base + hh*4 + {0..3} and row_base + 8 + hh*4 + {0..3}.
-// (ds_read_b64_tr_b16: within 16 lanes, lane i receives element i%4 of the 8-byte pieces addressed by
-// lanes i/4, i/4+4, i/4+8, i/4+12; here piece s of a group is row s/4, columns 4*(s%4)..+3.)
+// LDS operand that pairs with pack8, gathered from a row-major [row][col] tile with the LDS transpose read:
+// MFMA row (lane % 32) = tile column col_base + lane % 32, and the 8 k-slots of lane half hh = tile rows
+// row_base + hh*4 + {0..3} and row_base + 8 + hh*4 + {0..3}.  (ds_read_b64_tr_b16: within 16 lanes, lane i
+// receives element i%4 of the 8-byte pieces addressed by lanes i/4, i/4+4, i/4+8, i/4+12; here piece s of a
+// group is row s/4, columns 4*(s%4)..+3.)  The kernels below form the two addresses of such an operand from
+// per-lane constants (p3_base) of the permuted tile layout.
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
-__device__ __forceinline__ bf16x8 read_tr(const char* tile, int RS, int col_base, int row_base, int lane) {
-  const int g16 = (lane >> 4) & 1, hh = lane >> 5, sl = lane & 15;
-  const char* p = tile + (row_base + hh * 4 + (sl >> 2)) * RS + (col_base + g16 * 16 + (sl & 3) * 4) * 2;
-  typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
-  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 8 * RS));
-  const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-  return __builtin_bit_cast(bf16x8, v);
-}
 
 // Workgroups are dealt to the 8 XCDs (each with its own L2) in turn: linear id L runs on XCD L % 8.
 // Longest blocks first over the whole launch: linear id L -> (level, sequence, head) with the level (which
@@ -95,43 +86,6 @@ __device__ __forceinline__ void unrotate4(float (&v)[4], const float* __restrict
   v[2] = a1 * cs.z + b1 * cs.w;
   v[3] = b1 * cs.z - a1 * cs.w;
 }
-
-// ---- staging of a [ROWS x HD] block of a row-major matrix (row stride ld elements): 16-byte chunks,
-// consecutive lanes take consecutive chunks of a row.  NCH chunks per thread (256 threads).
-template <int HD, int ROWS>
-struct Stage {
-  static constexpr int kChunksPerRow = HD / 8;
-  static constexpr int kChunks = ROWS * kChunksPerRow;
-  static constexpr int NCH = (kChunks + 255) / 256;
-  __device__ __forceinline__ static void load(u32x4 (&reg)[NCH], const bf16* __restrict__ X, int64_t ld, int row0, int row_max, int tid) {
-#pragma unroll
-    for (int n = 0; n < NCH; ++n) {
-      const int c = tid + 256 * n;
-      if (kChunks % 256 == 0 || c < kChunks) {
-        const int r = min(row0 + c / kChunksPerRow, row_max);
-        reg[n] = *reinterpret_cast<const u32x4*>(X + (int64_t)r * ld + (c % kChunksPerRow) * 8);
-      }
-    }
-  }
-  // the same block through a buffer descriptor: voff0(tid) + row0 * row_bytes; rows past the end read as zero
-  __device__ __forceinline__ static uint32_t voff0(int tid, int n, uint32_t row_bytes) {
-    const int c = tid + 256 * n;
-    return (uint32_t)(c / kChunksPerRow) * row_bytes + (uint32_t)(c % kChunksPerRow) * 16u;
-  }
-  __device__ __forceinline__ static void bload(u32x4 (&reg)[NCH], rsrc_t rsrc, uint32_t row_bytes, uint32_t off, int tid) {
-#pragma unroll
-    for (int n = 0; n < NCH; ++n)
-      if (kChunks % 256 == 0 || tid + 256 * n < kChunks) reg[n] = buffer_load16(rsrc, voff0(tid, n, row_bytes) + off);
-  }
-  __device__ __forceinline__ static void store(const u32x4 (&reg)[NCH], char* tile, int stride, int tid) {
-#pragma unroll
-    for (int n = 0; n < NCH; ++n) {
-      const int c = tid + 256 * n;
-      if (kChunks % 256 == 0 || c < kChunks)
-        *reinterpret_cast<u32x4*>(tile + (c / kChunksPerRow) * stride + (c % kChunksPerRow) * 16) = reg[n];
-    }
-  }
-};
 
 // Geometry of the unpadded row-major [rows][HD] tiles that direct-to-LDS loads fill (used by the ring forward
 // kernel for K and V and by the dK/dV kernel for Q and dO), with the chunk permutation that makes row-wise
@@ -231,7 +185,7 @@ __global__ __launch_bounds__(256, 2) void k_flash_fwd(const bf16* __restrict__ q
   // ---- lane constants of the LDS reads
   // K, row-wise: key row lq (+32 for the tile's second half), chunk 2 kk + hh permuted; kk enters by XOR with kk * 32
   const int p1_base = lq * RB + ((hh ^ G::key(lq)) << 4);
-  // V, transpose reads (see read_tr): rows 16 tu + 8 hi + 4 hh + i, chunks 4 c + w; c enters by XOR with c * 64
+  // V, transpose reads (see pack8): rows 16 tu + 8 hi + 4 hh + i, chunks 4 c + w; c enters by XOR with c * 64
   int p3_base[2];
   {
     const int sl = lane & 15, i = sl >> 2, w = ((lane >> 4) & 1) * 2 + ((sl & 3) >> 1), half = sl & 1;
@@ -405,117 +359,156 @@ __global__ __launch_bounds__(256) void k_flash_delta(const bf16* __restrict__ o,
 // ================================================================================ backward: dQ
 // Same walk as the forward.  Per tile: S^T = K Q^T, P = exp(S - lse), dP^T = V dO^T,
 // dS^T = P (dP^T - delta), dQ^T[col][query] += K^T dS^T.  The 1/sqrt(hd) factor is applied at the end.
+// K and V tiles arrive as in the forward kernel (direct-to-LDS loads into rings of two tiles each, one barrier per
+// tile); the one copy of a K tile serves both the row-wise reads of the first product and the transpose reads of
+// the last (DkvGeom::key).
 template <int HD>
 __global__ __launch_bounds__(256, 2) void k_flash_bwd_dq(const bf16* __restrict__ qkv, const bf16* __restrict__ dO,
                                                          const float* __restrict__ lse, const float* __restrict__ delta,
                                                          bf16* __restrict__ dqkv, int T, int H, int Hkv, float scale,
                                                          const float* __restrict__ rope_tab) {
-  constexpr int BQ = 128, BKV = 64;
-  constexpr int KS = HD * 2 + 16;   // K and V tiles [key][hd]
-  constexpr int TS = HD * 2 + 64;   // second copy of K, [key][hd], strided for the transpose read
-  constexpr int kKTile = BKV * KS, kTTile = BKV * TS;
-  __shared__ __attribute__((aligned(16))) char smem[2 * kKTile + kTTile];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lq = lane & 31, hh = lane >> 5;
+  typedef DkvGeom<HD> G;
+  constexpr int BQ = 128, BKV = 64, RB = G::RB, CPR = G::CPR;
+  constexpr int kTile = BKV * RB;
+  constexpr int NJ = kTile / 4096;
+  constexpr int NK = HD / 16, NC = HD / 32;
+  __shared__ __attribute__((aligned(1024))) char smem[4 * kTile];
+  char* const k_ring = smem;
+  char* const v_ring = smem + 2 * kTile;
+  const int tid = threadIdx.x, lane = tid & 63, lq = lane & 31, hh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int nqb = (T + 127) / 128;
   const BlockId id = heavy_first(blockIdx.x, (int)gridDim.x / (nqb * H), H);   // heaviest query blocks first
   const int qb = nqb - 1 - id.level, a = id.a, b = id.b;
   const int kvh = a / (H / Hkv);
   const int64_t ld = (int64_t)(H + 2 * Hkv) * HD;
   const bf16* Q = qkv + (int64_t)b * T * ld + a * HD;
-  const bf16* Kp = qkv + (int64_t)b * T * ld + (H + kvh) * HD;
-  const bf16* Vp = qkv + (int64_t)b * T * ld + (H + Hkv + kvh) * HD;
   const int q0 = qb * BQ, qw0 = q0 + wave * 32, q = qw0 + lq, qc = min(q, T - 1);
   const float scale_log2 = scale * kLog2e;
 
-  bf16x8 qf[HD / 16], dof[HD / 16];
+  bf16x8 qf[NK], dof[NK];
   {
     const bf16* qr = Q + (int64_t)qc * ld + hh * 8;
     const bf16* dr = dO + ((int64_t)b * T + qc) * H * HD + a * HD + hh * 8;
 #pragma unroll
-    for (int kk = 0; kk < HD / 16; ++kk) {
+    for (int kk = 0; kk < NK; ++kk) {
       qf[kk] = *reinterpret_cast<const bf16x8*>(qr + kk * 16);
       dof[kk] = *reinterpret_cast<const bf16x8*>(dr + kk * 16);
     }
   }
   const float lse2 = lse[((int64_t)b * H + a) * T + qc] * kLog2e;
   const float dlt = delta[((int64_t)b * H + a) * T + qc];
-  f32x16 dq[HD / 32];
+  f32x16 dq[NC];
 #pragma unroll
-  for (int c = 0; c < HD / 32; ++c) dq[c] = zero16();
+  for (int c = 0; c < NC; ++c) dq[c] = zero16();
 
-  char* ks = smem;
-  char* vs = smem + kKTile;
-  char* kts = smem + 2 * kKTile;
   const int kv_end = min(T, q0 + BQ);
   const int ntiles = (kv_end + BKV - 1) / BKV;
-  typedef Stage<HD, BKV> ST;
-  u32x4 rk[ST::NCH], rv[ST::NCH];
-  ST::load(rk, Kp, ld, 0, T - 1, tid);
-  ST::load(rv, Vp, ld, 0, T - 1, tid);
+
+  // ---- tile loads and LDS read offsets: as in the forward kernel
+  const uint32_t row_bytes = (uint32_t)ld * 2u;
+  uint32_t ldo[NJ];
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int c = (4 * j + wave) * 64 + lane, row = c / CPR, pos = c % CPR;
+    ldo[j] = (uint32_t)row * row_bytes + (uint32_t)((pos ^ G::key(row)) << 4);
+  }
+  const u32x4 rs = make_desc(qkv + (int64_t)b * T * ld, (uint32_t)((int64_t)T * ld * 2));   // this sequence's rows
+  const uint32_t k_col = (uint32_t)(H + kvh) * HD * 2u, v_col = (uint32_t)(H + Hkv + kvh) * HD * 2u;
+  auto load_kv = [&](int kt) {
+    char* kd = k_ring + (kt & 1) * kTile;
+    char* vd = v_ring + (kt & 1) * kTile;
+    const uint32_t off = (uint32_t)kt * BKV * row_bytes;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      load_to_lds16(rs, (lds_ptr)(kd + (4 * j + wave) * 1024), ldo[j] + off + k_col);
+      load_to_lds16(rs, (lds_ptr)(vd + (4 * j + wave) * 1024), ldo[j] + off + v_col);
+    }
+  };
+  auto landed_barrier = [&]() {
+    __builtin_amdgcn_s_waitcnt(0 | (7 << 4) | (0 << 8));   // vmcnt(0) lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
+  };
+  const int p1_base = lq * RB + ((hh ^ G::key(lq)) << 4);
+  int p3_base[2];
+  {
+    const int sl = lane & 15, i = sl >> 2, w = ((lane >> 4) & 1) * 2 + ((sl & 3) >> 1), half = sl & 1;
+#pragma unroll
+    for (int hi = 0; hi < 2; ++hi) {
+      const int row = 8 * hi + 4 * hh + i;
+      p3_base[hi] = row * RB + (((G::key(row) & 12) | (w ^ (G::key(row) & 3))) << 4) + half * 8;
+    }
+  }
+  typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+  // K^T fragment for the last product: tile rows (keys) 16 u2 + .., columns 32 c + ..
+  auto read_kt = [&](const char* kt_base, int u2, int c) {
+    const char* base = kt_base + 16 * u2 * RB;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(base + (p3_base[0] ^ (c * 64))));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(base + (p3_base[1] ^ (c * 64))));
+    const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8, v);
+  };
+
+  load_kv(0);
+  landed_barrier();
   // one tile; MASKED: some key of the tile may lie past some query of the workgroup (its last two tiles)
   auto tile_step = [&](int kt, auto masked_tag) {
     constexpr bool MASKED = decltype(masked_tag)::value;
     const int k0 = kt * BKV;
-    ST::store(rk, ks, KS, tid);
-    ST::store(rk, kts, TS, tid);
-    ST::store(rv, vs, KS, tid);
-    __syncthreads();
-    {
-      const int kn = min(k0 + BKV, (ntiles - 1) * BKV);   // straight-line body, as in the forward kernel
-      ST::load(rk, Kp, ld, kn, T - 1, tid);
-      ST::load(rv, Vp, ld, kn, T - 1, tid);
-    }
-    {
+    // into the buffers read in the iteration before, which ended at a barrier; past the last tile the rows are
+    // never read (or zeros past the end of the sequence)
+    load_kv(kt + 1);
+    const char* kt_base = k_ring + (kt & 1) * kTile;
+    const char* vt_base = v_ring + (kt & 1) * kTile;
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        // S^T and dP^T as two independent MFMA chains; K and V fragments fetched two k-steps ahead
-        f32x16 st = zero16(), dp = zero16();
-        bf16x8 fb[2][4];
-        const char* kr = ks + (t * 32 + lq) * KS + hh * 16;
-        const char* vr = vs + (t * 32 + lq) * KS + hh * 16;
-        auto ldkv = [&](int g, bf16x8 (&f)[4]) {
-          f[0] = *reinterpret_cast<const bf16x8*>(kr + (2 * g) * 32);
-          f[1] = *reinterpret_cast<const bf16x8*>(vr + (2 * g) * 32);
-          f[2] = *reinterpret_cast<const bf16x8*>(kr + (2 * g + 1) * 32);
-          f[3] = *reinterpret_cast<const bf16x8*>(vr + (2 * g + 1) * 32);
-        };
-        auto ldt = [&](int u, bf16x8 (&f)[4]) {
+    for (int t = 0; t < 2; ++t) {
+      // S^T and dP^T as two independent MFMA chains; K and V fragments fetched a k-step pair ahead
+      f32x16 st = zero16(), dp = zero16();
+      bf16x8 fb[2][4];
+      const char* kr = kt_base + t * 32 * RB;
+      const char* vr = vt_base + t * 32 * RB;
+      auto ldkv = [&](int g, bf16x8 (&f)[4]) {
+        f[0] = *reinterpret_cast<const bf16x8*>(kr + (p1_base ^ ((2 * g) * 32)));
+        f[1] = *reinterpret_cast<const bf16x8*>(vr + (p1_base ^ ((2 * g) * 32)));
+        f[2] = *reinterpret_cast<const bf16x8*>(kr + (p1_base ^ ((2 * g + 1) * 32)));
+        f[3] = *reinterpret_cast<const bf16x8*>(vr + (p1_base ^ ((2 * g + 1) * 32)));
+      };
+      auto ldt = [&](int u, bf16x8 (&f)[4]) {
 #pragma unroll
-          for (int c = 0; c < HD / 32; ++c) f[c] = read_tr(kts, TS, c * 32, t * 32 + 16 * u, lane);
-        };
-        ldkv(0, fb[0]);
+        for (int c = 0; c < NC; ++c) f[c] = read_kt(kt_base, 2 * t + u, c);
+      };
+      ldkv(0, fb[0]);
 #pragma unroll
-        for (int g = 0; g < HD / 32; ++g) {
-          if (g + 1 < HD / 32) ldkv(g + 1, fb[(g + 1) & 1]);
-          __builtin_amdgcn_sched_barrier(0);
-          st = mfma(fb[g & 1][0], qf[2 * g], st);
-          dp = mfma(fb[g & 1][1], dof[2 * g], dp);
-          st = mfma(fb[g & 1][2], qf[2 * g + 1], st);
-          dp = mfma(fb[g & 1][3], dof[2 * g + 1], dp);
-          __builtin_amdgcn_sched_barrier(0);
-        }
-        ldt(0, fb[0]);
+      for (int g = 0; g < NC; ++g) {
+        if (g + 1 < NC) ldkv(g + 1, fb[(g + 1) & 1]);
         __builtin_amdgcn_sched_barrier(0);
+        st = mfma(fb[g & 1][0], qf[2 * g], st);
+        dp = mfma(fb[g & 1][1], dof[2 * g], dp);
+        st = mfma(fb[g & 1][2], qf[2 * g + 1], st);
+        dp = mfma(fb[g & 1][3], dof[2 * g + 1], dp);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      ldt(0, fb[0]);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(st[r], scale_log2, -lse2));
-          if (MASKED) {
-            const int key = k0 + t * 32 + (r >> 2) * 8 + hh * 4 + (r & 3);
-            if (key > q) pv = 0.f;
-          }
-          st[r] = pv * (dp[r] - dlt);
+      for (int r = 0; r < 16; ++r) {
+        float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(st[r], scale_log2, -lse2));
+        if (MASKED) {
+          const int key = k0 + t * 32 + (r >> 2) * 8 + hh * 4 + (r & 3);
+          if (key > q) pv = 0.f;
         }
+        st[r] = pv * (dp[r] - dlt);
+      }
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-          if (u + 1 < 2) ldt(u + 1, fb[(u + 1) & 1]);
-          __builtin_amdgcn_sched_barrier(0);
-          const bf16x8 dsf = pack8(st, u);
+      for (int u = 0; u < 2; ++u) {
+        if (u + 1 < 2) ldt(u + 1, fb[(u + 1) & 1]);
+        __builtin_amdgcn_sched_barrier(0);
+        const bf16x8 dsf = pack8(st, u);
 #pragma unroll
-          for (int c = 0; c < HD / 32; ++c) dq[c] = mfma(fb[u & 1][c], dsf, dq[c]);
-        }
+        for (int c = 0; c < NC; ++c) dq[c] = mfma(fb[u & 1][c], dsf, dq[c]);
       }
     }
-    __syncthreads();
+    landed_barrier();
   };
   const int n_free = min(ntiles, q0 / BKV);   // tiles that end before the workgroup's first query: no mask
   for (int kt = 0; kt < n_free; ++kt) tile_step(kt, std::false_type());
@@ -523,7 +516,7 @@ __global__ __launch_bounds__(256, 2) void k_flash_bwd_dq(const bf16* __restrict_
   if (q < T) {
     bf16* row = dqkv + ((int64_t)b * T + q) * ld + a * HD;
 #pragma unroll
-    for (int c = 0; c < HD / 32; ++c)
+    for (int c = 0; c < NC; ++c)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         uint2 w;
@@ -615,7 +608,7 @@ __global__ __launch_bounds__(256) void k_flash_bwd_dkv(const bf16* __restrict__ 
   // ---- lane constants of the LDS reads (byte offsets inside a ring buffer)
   // phase 1: row lk, chunk (2 kk + hh) permuted; kk enters by XOR with kk * 32
   const int p1_base = lk * RB + ((hh ^ G::key(lk)) << 4);
-  // phase 3 (transpose reads, see read_tr): 16-lane group position i = row, w = chunk, half = 8-byte half;
+  // phase 3 (transpose reads, see pack8): 16-lane group position i = row, w = chunk, half = 8-byte half;
   // rows 16u + 8hi + 4hh + i, chunks 4c + w.  u enters as a constant offset, c by XOR with c * 64.
   int p3_base[2];
   {
