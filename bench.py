@@ -25,7 +25,7 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 # FETCH_SIZE (x 1.998, the factor a plain copy of known size gives) + WRITE_SIZE (x 1.000); see
 # profiles/c3_stage_counters_pmc.txt.  Valid for the kernel as it was when the counters were taken: set to None
 # when k_gemm_mfma changes.
-GEMM_TN_C3_TRAFFIC_BYTES = 593.3e6
+GEMM_TN_C3_TRAFFIC_BYTES = 599.1e6
 
 
 def flops_per_token_layer(cfg):
