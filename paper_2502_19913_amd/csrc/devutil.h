@@ -43,12 +43,11 @@ __device__ __forceinline__ void unpack8(const uint4& v, float (&x)[8]) {
 #pragma unroll
   for (int e = 0; e < 4; ++e) { x[2 * e] = bf16_bits_to_float(w[e] & 0xffffu); x[2 * e + 1] = bf16_bits_to_float(w[e] >> 16); }
 }
-// Tells the compiler that the four registers may have changed: values derived from them before this point are
-// not kept alive for reuse after it (a kernel that holds many packed values and unpacks them in two passes would
-// otherwise keep the unpacked floats of the first pass, at twice the registers).
-__device__ __forceinline__ void forget_derived(uint4& v) { asm volatile("" : "+v"(v.x), "+v"(v.y), "+v"(v.z), "+v"(v.w)); }
-// The same, and nothing derived from v after this point is computed before `after` has its value: keeps the
-// pieces of an unrolled loop in sequence where the scheduler would otherwise unpack all of them at once.
+// Tells the compiler that the four registers (and `after`) may have changed: values derived from them before this
+// point are not kept alive for reuse after it (a kernel that holds many packed values and unpacks them in several
+// passes would otherwise keep the unpacked floats of the first pass, at twice the registers), and nothing derived
+// from v after this point is computed before `after` has its value, which keeps the pieces of an unrolled loop in
+// sequence where the scheduler would otherwise unpack all of them at once.
 __device__ __forceinline__ void forget_derived(uint4& v, float& after) {
   asm volatile("" : "+v"(v.x), "+v"(v.y), "+v"(v.z), "+v"(v.w), "+v"(after));
 }
