@@ -339,10 +339,11 @@ int sp_grad_reduce(void* hip_stream, const float* const* replica_grads, int n_re
  * launch of this process is bracketed by HIP events on its stream.  sp_prof_end waits for them and
  * fills, per kernel class c < n_classes, the summed duration (ms), the summed algorithmic flops
  * and the launch count (host arrays).  Classes: 0 C=A B^T, 1 C=A B, 2 C+=A^T B (MFMA kernels),
- * 3 attention forward, 4 attention delta, 5 attention dQ, 6 attention dK/dV, 7 plain matrix
+ * 3 attention forward, 4 attention delta (see below), 5 attention dQ, 6 attention dK/dV, 7 plain matrix
  * product, 8 plain attention; and the bandwidth-bound kernels, whose "flops" entry holds algorithmic
- * BYTES instead: 9 RMSNorm forward, 10 RMSNorm backward, 11 cross-entropy, 12 slot gather / scatter,
- * 13 SwiGLU as a pass of its own (float mode, odd shapes). */
+ * BYTES instead: 4 attention delta (rows of o and dO read, one float per row and head written), 9 RMSNorm
+ * forward, 10 RMSNorm backward, 11 cross-entropy, 12 slot gather / scatter, 13 SwiGLU as a pass of its own
+ * (float mode, odd shapes). */
 int sp_prof_begin(void);
 int sp_prof_end(int n_classes, double* ms, double* flops, int64_t* launches);
 

@@ -365,7 +365,7 @@ def probe_mfma_rate(src, n_blocks, iters, sink, stream=None):
 
 PROF_CLASSES = ["gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd", "attn_delta", "attn_dq", "attn_dkv", "gemm_plain",
                 "attn_plain", "rmsnorm_fwd", "rmsnorm_bwd", "cross_entropy", "copy_rows", "swiglu"]
-PROF_BYTES_CLASSES = ("rmsnorm_fwd", "rmsnorm_bwd", "cross_entropy", "copy_rows", "swiglu")   # "flops" holds bytes
+PROF_BYTES_CLASSES = ("attn_delta", "rmsnorm_fwd", "rmsnorm_bwd", "cross_entropy", "copy_rows", "swiglu")   # "flops" holds bytes
 
 
 def prof_begin():

@@ -845,7 +845,7 @@ void attention_flash_bwd(hipStream_t s, int B, int T, int H, int Hkv, int hd, co
   else
     hipLaunchKernelGGL(k_flash_delta<64>, dim3((unsigned)((items * 8 + 255) / 256)), dim3(256), 0, s, (const bf16*)o,
                        (const bf16*)do_, B, T, H, delta);
-  prof_stop(pi, s, 0.0);
+  prof_stop(pi, s, (double)items * (2.0 * hd * 2 + 4));   // bytes: o and dO read, delta written
   pi = prof_start(PROF_ATTN_DQ, s);
   if (hd == 128)
     hipLaunchKernelGGL(k_flash_bwd_dq<128>, gq, dim3(256), 0, s, (const bf16*)qkv, (const bf16*)do_, lse, delta,
